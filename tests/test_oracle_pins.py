@@ -1,0 +1,325 @@
+"""Pins for the CPU oracle: each check ties it to something other than itself
+(brute force, closed forms, a library routine, finite differences, invariants,
+the numbers printed in the paper's Zig-Zag figure caption)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fcp_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape)
+
+
+def _brute_fwd(q, k, v, causal, scale):
+    """Triple-loop softmax attention in Python floats."""
+    Lq, Hq, d = q.shape
+    Lk, Hkv, _ = k.shape
+    o = [[[0.0] * d for _ in range(Hq)] for _ in range(Lq)]
+    lse = [[0.0] * Hq for _ in range(Lq)]
+    for i in range(Lq):
+        for h in range(Hq):
+            g = h // (Hq // Hkv)
+            js = [j for j in range(Lk) if (not causal or j <= i)]
+            s = [scale * sum(float(q[i, h, c]) * float(k[j, g, c]) for c in range(d)) for j in js]
+            tot = sum(math.exp(x) for x in s)
+            lse[i][h] = math.log(tot)
+            for c in range(d):
+                o[i][h][c] = sum(math.exp(x) / tot * float(v[j, g, c]) for x, j in zip(s, js))
+    return np.array(o), np.array(lse)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2), (4, 1)])
+def test_fwd_matches_brute_force(causal, hq, hkv):
+    rng = np.random.default_rng(7)
+    L, d = 11, 5
+    q, k, v = _rand(rng, L, hq, d), _rand(rng, L, hkv, d), _rand(rng, L, hkv, d)
+    o, lse = orc.attention_fwd_seq(q, k, v, causal, row_chunk=4)
+    ob, lb = _brute_fwd(q, k, v, causal, 1 / math.sqrt(d))
+    assert np.max(np.abs(o - ob)) < 1e-12
+    assert np.max(np.abs(lse - lb)) < 1e-12
+
+
+def test_fwd_rows_of_p_sum_to_one():
+    rng = np.random.default_rng(1)
+    L, H, d = 37, 3, 8
+    q, k = _rand(rng, L, H, d), _rand(rng, L, H, d)
+    o, _ = orc.attention_fwd_seq(q, k, np.ones((L, H, d)), True)
+    assert np.max(np.abs(o - 1.0)) < 1e-14
+
+
+def test_fwd_closed_form_equal_keys():
+    rng = np.random.default_rng(2)
+    L, H, d = 23, 2, 6
+    q, v = _rand(rng, L, H, d), _rand(rng, L, H, d)
+    k0 = _rand(rng, H, d)
+    k = np.broadcast_to(k0, (L, H, d)).copy()
+    o, lse = orc.attention_fwd_seq(q, k, v, True)
+    scale = 1 / math.sqrt(d)
+    for i in range(L):
+        assert np.allclose(o[i], v[: i + 1].mean(axis=0), atol=1e-13)
+        assert np.allclose(lse[i], scale * np.sum(q[i] * k0, axis=-1) + math.log(i + 1), atol=1e-13)
+
+
+def test_fwd_single_token():
+    rng = np.random.default_rng(3)
+    q, k, v = _rand(rng, 1, 4, 8), _rand(rng, 1, 2, 8), _rand(rng, 1, 2, 8)
+    o, lse = orc.attention_fwd_seq(q, k, v, True)
+    assert np.allclose(o[0], np.repeat(v[0], 2, axis=0), atol=0)
+    assert np.allclose(lse[0], np.sum(q[0] * np.repeat(k[0], 2, axis=0), -1) / math.sqrt(8), atol=1e-15)
+
+
+def _sdpa(q, k, v, causal):
+    Hq, Hkv = q.shape[1], k.shape[1]
+    tq = torch.tensor(q).permute(1, 0, 2)[None]
+    tk = torch.tensor(k).permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    tv = torch.tensor(v).permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    return tq, tk, tv
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_fwd_matches_library_sdpa(causal):
+    rng = np.random.default_rng(4)
+    L, Hq, Hkv, d = 70, 4, 2, 16
+    q, k, v = _rand(rng, L, Hq, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hkv, d)
+    tq, tk, tv = _sdpa(q, k, v, causal)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal)[0].permute(1, 0, 2).numpy()
+    o, _ = orc.attention_fwd_seq(q, k, v, causal, row_chunk=32)
+    assert np.max(np.abs(o - ref)) < 1e-12
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_bwd_matches_library_autograd(causal):
+    rng = np.random.default_rng(5)
+    L, Hq, Hkv, d = 45, 4, 2, 8
+    q, k, v, do = _rand(rng, L, Hq, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hq, d)
+    tq = torch.tensor(q, requires_grad=True)
+    tk = torch.tensor(k, requires_grad=True)
+    tv = torch.tensor(v, requires_grad=True)
+    a = tq.permute(1, 0, 2)[None]
+    b = tk.permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    c = tv.permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    out = torch.nn.functional.scaled_dot_product_attention(a, b, c, is_causal=causal)[0].permute(1, 0, 2)
+    (out * torch.tensor(do)).sum().backward()
+    dq, dk, dv = orc.attention_bwd_seq(q, k, v, do, causal, row_chunk=16)
+    assert np.max(np.abs(dq - tq.grad.numpy())) < 1e-12
+    assert np.max(np.abs(dk - tk.grad.numpy())) < 1e-12
+    assert np.max(np.abs(dv - tv.grad.numpy())) < 1e-12
+
+
+def test_bwd_finite_differences():
+    rng = np.random.default_rng(6)
+    L, Hq, Hkv, d = 9, 2, 1, 4
+    q, k, v, do = _rand(rng, L, Hq, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hq, d)
+    dq, dk, dv = orc.attention_bwd_seq(q, k, v, do, True)
+
+    def loss(q_, k_, v_):
+        return float(np.sum(orc.attention_fwd_seq(q_, k_, v_, True)[0] * do))
+
+    eps = 1e-6
+    for arr, grad, which in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args_hi = [q, k, v]
+            args_lo = [q, k, v]
+            args_hi[which], args_lo[which] = hi, lo
+            num[idx] = (loss(*args_hi) - loss(*args_lo)) / (2 * eps)
+        assert np.max(np.abs(num - grad)) / max(1.0, np.max(np.abs(grad))) < 1e-6
+
+
+def test_bwd_invariants():
+    rng = np.random.default_rng(8)
+    L, Hq, Hkv, d = 33, 4, 2, 8
+    q, k, v, do = _rand(rng, L, Hq, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hkv, d), _rand(rng, L, Hq, d)
+    dq, dk, dv = orc.attention_bwd_seq(q, k, v, do, True)
+    # softmax is shift invariant along the key axis: the key gradients of a KV head sum to zero
+    assert np.max(np.abs(dk.sum(axis=0))) < 1e-12
+    # rows of P sum to one: dV summed over keys equals dO summed over rows and the group's heads
+    want = do.reshape(L, Hkv, Hq // Hkv, d).sum(axis=(0, 2))
+    assert np.max(np.abs(dv.sum(axis=0) - want)) < 1e-12
+    z = orc.attention_bwd_seq(q, k, v, np.zeros_like(do), True)
+    assert all(np.all(t == 0) for t in z)
+
+
+def _bits(rng, *shape):
+    from paper_2605_08524_amd.workloads import bf16_bits
+    return bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+
+@pytest.mark.parametrize("bs,c", [(4, 1), (5, 2), (8, 0), (3, 3), (64, 16)])
+@pytest.mark.parametrize("causal", [1, 0])
+def test_block_partials_merge_to_whole(bs, c, causal):
+    """Associativity stated in section "Context Parallelism": partial results over
+    slices of the context reduce to the whole-sequence result."""
+    rng = np.random.default_rng(9)
+    seq_lens = [13, 1, 8, 0, 21, 5]
+    T, Hq, Hkv, d = sum(seq_lens), 4, 2, 8
+    q, k, v = _bits(rng, T, Hq, d), _bits(rng, T, Hkv, d), _bits(rng, T, Hkv, d)
+    plan = orc.plan_blocks(seq_lens, bs, causal, c)
+    op, lp = orc.partial_fwd(q, k, v, plan, bs, causal)
+    o, lse = orc.merge_partials(op, lp, plan)
+    ow, lw = orc.worker_fwd(q, k, v, seq_lens, bs, causal)
+    assert np.max(np.abs(o - ow)) < 1e-12
+    assert np.max(np.abs(lse - lw)) < 1e-12
+
+
+def test_share_of_owned_blocks():
+    rng = np.random.default_rng(10)
+    seq_lens, bs = [19, 7, 30], 4
+    T, Hq, Hkv, d = sum(seq_lens), 2, 1, 4
+    k, v = _bits(rng, T, Hkv, d), _bits(rng, T, Hkv, d)
+    qfull, dofull = _bits(rng, T, Hq, d), _bits(rng, T, Hq, d)
+    full = orc.plan_blocks(seq_lens, bs, 1, 2)
+    owned_a = [(0, 1), (0, 4), (2, 0), (2, 7)]
+    owned_b = [(int(s), int(i)) for s, i, _, _ in full["kv_blocks"] if (int(s), int(i)) not in owned_a]
+
+    def rows_of(owned):
+        r = []
+        for s, i in owned:
+            base = sum(seq_lens[:s]) + i * bs
+            r += list(range(base, min(base + bs, sum(seq_lens[: s + 1]))))
+        return np.array(r)
+
+    ofull, lfull = orc.worker_fwd(qfull, k, v, seq_lens, bs, 1)
+    dqf, dkf, dvf = orc.worker_bwd(qfull, k, v, dofull, seq_lens, bs, 1)
+    dk_sum = np.zeros_like(dkf)
+    dv_sum = np.zeros_like(dvf)
+    for owned in (owned_a, owned_b):
+        rows = rows_of(owned)
+        plan = orc.plan_blocks(seq_lens, bs, 1, 2, owned)
+        assert plan["q_blocks"][:, 3].sum() == len(rows)
+        o, lse = orc.worker_fwd(qfull[rows], k, v, seq_lens, bs, 1, owned)
+        assert np.max(np.abs(o - ofull[rows])) < 1e-13 and np.max(np.abs(lse - lfull[rows])) < 1e-13
+        op, lp = orc.partial_fwd(qfull[rows], k, v, plan, bs, 1)
+        om, lm = orc.merge_partials(op, lp, plan)
+        assert np.max(np.abs(om - ofull[rows])) < 1e-12 and np.max(np.abs(lm - lfull[rows])) < 1e-12
+        sample = np.arange(0, len(rows), 3)
+        orow, lrow = orc.rows_fwd(qfull[rows], k, v, seq_lens, bs, plan, sample, 1)
+        assert np.max(np.abs(orow - ofull[rows][sample])) < 1e-13
+        assert np.max(np.abs(lrow - lfull[rows][sample])) < 1e-13
+        dq, dk, dv = orc.worker_bwd(qfull[rows], k, v, dofull[rows], seq_lens, bs, 1, owned)
+        assert np.max(np.abs(dq - dqf[rows])) < 1e-12
+        dk_sum += dk
+        dv_sum += dv
+    assert np.max(np.abs(dk_sum - dkf)) < 1e-12 and np.max(np.abs(dv_sum - dvf)) < 1e-12
+
+
+def test_merge_handles_empty_partials():
+    plan = orc.plan_blocks([4], 2, 1, 1)
+    n = plan["n_slot_rows"]
+    o = np.ones((n, 1, 2))
+    lse = np.full((n, 1), -np.inf)
+    om, lm = orc.merge_partials(o, lse, plan)
+    assert np.all(om == 0) and np.all(np.isneginf(lm))
+    # q block 1 has two slots; make the first one empty, the second one carries the result
+    lse2 = np.zeros((n, 1))
+    r_first = int(plan["slots"][1][3])
+    lse2[r_first:r_first + 2] = -np.inf
+    o2 = np.arange(n * 2, dtype=np.float64).reshape(n, 1, 2)
+    om, lm = orc.merge_partials(o2, lse2, plan)
+    r_second = int(plan["slots"][2][3])
+    assert np.array_equal(om[2:4], o2[r_second:r_second + 2]) and np.all(lm[2:4] == 0)
+
+
+def _golden():
+    out = {}
+    with open(os.path.join(GOLDEN, "zigzag_figure_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k_, v_ = line.split()
+                out[k_] = int(v_)
+    return out
+
+
+def test_planner_zigzag_figure_counts():
+    g = _golden()
+    n, bs = g["n_blocks"], 16
+    plan = orc.plan_blocks([n * bs], bs, 1, 1)
+    pairs = plan["pairs"]
+    qi = g["q_index"]
+    mine = pairs[pairs[:, 0] == qi]
+    assert len(mine) == g["kv_blocks_needed_by_q"]
+    assert (mine[:, 2] == orc.DIAG).sum() == 1 and (mine[:, 2] == orc.FULL).sum() == len(mine) - 1
+    later = pairs[(pairs[:, 1] == qi) & (pairs[:, 0] != qi)]
+    assert len(later) == g["later_q_blocks_needing_kv"]
+    assert len(pairs) == n * (n + 1) // 2 and (pairs[:, 2] == orc.DIAG).sum() == n
+    # zig-zag partners (i, n-1-i) carry equal work: pairs(i) + pairs(n-1-i) = n + 1
+    for i in range(n // 2):
+        assert (pairs[:, 0] == i).sum() + (pairs[:, 0] == n - 1 - i).sum() == n + 1
+
+
+def test_planner_quadratic_compute_ratio():
+    g = _golden()
+    nnz = []
+    for L in (g["long_len"], g["short_len"]):
+        plan = orc.plan_blocks([L], 1024, 1, 16)
+        assert orc.pair_nnz(plan) == L * (L + 1) // 2
+        nnz.append(orc.pair_nnz(plan))
+    assert abs(nnz[0] / nnz[1] - g["compute_ratio"]) / g["compute_ratio"] < 1e-3
+
+
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("c", [0, 1, 2, 16])
+def test_planner_brute_force_coverage(causal, c):
+    """Every visible (query token, key token) entry is covered by exactly one pair,
+    masked entries by none; table bookkeeping is consistent."""
+    seq_lens, bs = [10, 3, 0, 17, 4, 1], 4
+    owned = None
+    plan = orc.plan_blocks(seq_lens, bs, causal, c, owned)
+    kvb, qb, pairs, slots = plan["kv_blocks"], plan["q_blocks"], plan["pairs"], plan["slots"]
+    assert kvb[:, 3].sum() == sum(seq_lens) and np.array_equal(kvb, qb)
+    assert np.array_equal(kvb[:, 2], np.concatenate([[0], np.cumsum(kvb[:-1, 3])]))
+    T = sum(seq_lens)
+    seq_of = np.repeat(np.arange(len(seq_lens)), seq_lens)
+    pos_of = np.concatenate([np.arange(L) for L in seq_lens])
+    want = (seq_of[:, None] == seq_of[None, :])
+    if causal:
+        want &= pos_of[None, :] <= pos_of[:, None]
+    got = np.zeros((T, T), dtype=np.int64)
+    for q_, k_, kind, slot in pairs:
+        _, _, qs, ql = qb[q_]
+        _, _, ks, kl = kvb[k_]
+        blk = np.ones((ql, kl), dtype=np.int64)
+        if kind == orc.DIAG:
+            assert q_ == k_ or (qb[q_][0] == kvb[k_][0] and qb[q_][1] == kvb[k_][1])
+            blk = np.tril(blk)
+        got[qs:qs + ql, ks:ks + kl] += blk
+        assert slots[slot][0] == q_
+    assert np.array_equal(got, want.astype(np.int64))
+    assert orc.pair_nnz(plan) == int(want.sum())
+    # canonical order and slot bookkeeping
+    key = pairs[:, 0].astype(np.int64) * (len(kvb) + 1) + pairs[:, 1]
+    assert np.all(np.diff(key) > 0)
+    assert np.array_equal(pairs[:, 3], np.repeat(np.arange(len(slots)), slots[:, 2]))
+    assert np.array_equal(slots[:, 1], np.concatenate([[0], np.cumsum(slots[:-1, 2])]))
+    if c:
+        assert slots[:, 2].max() <= c
+    rows = np.concatenate([[0], np.cumsum(qb[slots[:, 0], 3])])
+    assert np.array_equal(slots[:, 3], rows[:-1]) and plan["n_slot_rows"] == rows[-1]
+
+
+def test_planner_rejects_bad_input():
+    with pytest.raises(ValueError):
+        orc.plan_blocks([4], 0)
+    with pytest.raises(ValueError):
+        orc.plan_blocks([-1], 4)
+    with pytest.raises(ValueError):
+        orc.plan_blocks([8], 4, 1, 0, [(0, 2)])
+    with pytest.raises(ValueError):
+        orc.plan_blocks([8], 4, 1, 0, [(0, 1), (0, 0)])
+
+
+def test_flop_model():
+    plan = orc.plan_blocks([8], 4, 1, 0)
+    f, b = orc.flops(plan, 3, 16)
+    assert f == 4 * 16 * 3 * 36 and b == 10 * 16 * 3 * 36
