@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-attention hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch already resident in HBM:
+forward partials (fcp_block_attn_fwd) -> merge (fcp_merge_partials) -> backward preprocess
+(fcp_bwd_preprocess) -> backward (fcp_block_attn_bwd_main).  The default workload is the
+packed variable-length training step (64K tokens, 1024-token blocks, GQA 32/8, d = 128, bf16).
+
+Prints ONE JSON line: whole-step throughput in causal-adjusted TFLOP/s, the roofline of the
+dominant kernel measured with events on the launch stream, and the CPU oracle timed on a
+bounded sample of the same workload (a reported baseline only).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by a copy kernel of known size (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def pair_flops(plan, n_q_heads, head_dim):
+    """Causal-adjusted FLOPs from the pair table: 4 d per unmasked score entry and query head
+    forward (two contractions), 10 d backward (five)."""
+    qlen = plan["q_blocks"][:, 3].astype("int64")
+    klen = plan["kv_blocks"][:, 3].astype("int64")
+    pr = plan["pairs"]
+    m = qlen[pr[:, 0]]
+    n = klen[pr[:, 1]]
+    nnz = int(((pr[:, 2] == 0) * m * n + (pr[:, 2] == 1) * (m * (m + 1) // 2)).sum())
+    return 4 * head_dim * n_q_heads * nnz, 10 * head_dim * n_q_heads * nnz, nnz
+
+
+def cpu_baseline(wl, budget_s=20.0):
+    """Time the fp64 oracle (forward + backward, whole sequences) on the shortest sequences of
+    the workload until about `budget_s` seconds of CPU work are spent."""
+    import numpy as np
+    from oracle import fcp_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    q, k, v, do = wl.q(), wl.k(), wl.v(), wl.d_o()
+    offs = np.concatenate([[0], np.cumsum(wl.seq_lens.astype(np.int64))])
+    order = np.argsort(wl.seq_lens, kind="stable")
+    spent, flops, used = 0.0, 0, []
+    for s in order:
+        L = int(wl.seq_lens[s])
+        if L == 0:
+            continue
+        a, b = int(offs[s]), int(offs[s + 1])
+        t0 = time.perf_counter()
+        qs, ks, vs, ds = (orc.bf16_to_f64(x[a:b]) for x in (q, k, v, do))
+        orc.attention_fwd_seq(qs, ks, vs, True)
+        orc.attention_bwd_seq(qs, ks, vs, ds, True)
+        spent += time.perf_counter() - t0
+        flops += 14 * wl.head_dim * wl.n_q_heads * (L * (L + 1) // 2)
+        used.append(L)
+        if spent >= budget_s:
+            break
+    return {
+        "value": round(flops / spent / 1e12, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": f"fp64 numpy oracle fwd+bwd on the {len(used)} shortest sequences of the workload "
+                  f"({sum(used)} tokens, {flops / 1e9:.1f} causal-adjusted GFLOP) in {spent:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload: 5 = training step (default), 2/3/4 = forward only")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_08524_amd import FCP_FLAG_O_F32, fcp_device_info, workloads
+    from paper_2605_08524_amd.harness import DevicePath
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = workloads.make_workload(args.config, args.seed)
+    backward = args.config == 5
+    stream = torch.cuda.current_stream(dev)
+    t0 = time.perf_counter()
+    dp = DevicePath(wl, dev, flags=FCP_FLAG_O_F32 if backward else 0, backward=backward, stream=stream)
+    torch.cuda.synchronize(dev)
+    setup_s = time.perf_counter() - t0
+    f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
+    step_flops = f_fwd + (f_bwd if backward else 0)
+
+    stages = [("fwd", dp.fwd), ("merge", dp.merge)]
+    if backward:
+        stages += [("bwd_pre", dp.bwd_pre), ("bwd", dp.bwd_main)]
+
+    def step(events=None):
+        for i, (_, fn) in enumerate(stages):
+            if events is not None:
+                events[i][0].record(stream)
+            fn()
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize(dev)
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in stages]
+           for _ in range(args.steps)]
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize(dev)
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    stage_ms = {}
+    for i, (name, _) in enumerate(stages):
+        stage_ms[name] = sum(evs[s][i][0].elapsed_time(evs[s][i][1]) for s in range(args.steps)) / args.steps
+
+    # dominant kernel: the contraction kernel with the larger average duration
+    dom = "bwd" if backward and stage_ms["bwd"] >= stage_ms["fwd"] else "fwd"
+    dom_flops = f_bwd if dom == "bwd" else f_fwd
+    achieved = dom_flops / (stage_ms[dom] * 1e-3) / 1e12
+    p = dp.problem
+    merge_bytes = (p.n_slot_rows * wl.n_q_heads * (wl.head_dim * 4 + 4)
+                   + p.t_q * wl.n_q_heads * (wl.head_dim * (4 if backward else 2) + 4))
+    info = fcp_device_info()
+    out = {
+        "metric": "block-attention fwd+bwd TFLOP/s (causal-adj)" if backward else "block-attention fwd TFLOP/s (causal-adj)",
+        "value": round(step_flops / (ms_per_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": wl.name, "seed": args.seed, "tokens_q": p.t_q, "tokens_kv": p.t_kv,
+            "block_size": wl.block_size, "coalesce": wl.coalesce, "n_q_heads": wl.n_q_heads,
+            "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "n_seqs": int(len(wl.seq_lens)),
+            "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
+            "nnz_per_head": nnz, "o_dtype": "f32" if backward else "bf16", "parallelism": "single-gpu",
+        },
+        "frac_of_bf16_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "stage_tflops": {"fwd": round(f_fwd / stage_ms["fwd"] / 1e9, 2),
+                         **({"bwd": round(f_bwd / stage_ms["bwd"] / 1e9, 2)} if backward else {})},
+        "merge_gbs": round(merge_bytes / stage_ms["merge"] / 1e6, 1),
+        "roofline": {
+            "kernel": "bwd_kernel" if dom == "bwd" else "fwd_kernel",
+            "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)),
+            "avg_launch_ms": round(stage_ms[dom], 4),
+        },
+        "grid": info, "setup_s": round(setup_s, 2),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl) if backward else None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,189 @@
+/*
+ * fcp.h -- C ABI of the MI355X block-level attention library (one FCP worker).
+ *
+ * The paper splits every sequence of a batch into fixed-size blocks (section
+ * "Block Distributor", sharding policy), derives the (query block, KV block)
+ * dependencies from the attention mask (Zig-Zag figure caption; congestion-free
+ * solver figure), coalesces c consecutive KV blocks into one execution stage
+ * (section "Communication Planner", bottom-up coalescer), runs a flash-style
+ * attention kernel per stage and reduces the per-stage results to the final
+ * output (section "Context Parallelism": attention over slices of the context is
+ * associative).  This library is the part one worker executes once every KV
+ * block its dependencies name is resident in its HBM.
+ *
+ * Conventions for every entry point
+ *   - returns FCP_OK (0) or a negative fcp_status; never throws or aborts;
+ *     fcp_last_error() gives the text for the calling thread's last failure.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the current device.  The library allocates no device memory:
+ *     tensors, tables and the workspace are caller-allocated and caller-freed.
+ *   - kernels are enqueued on the given hipStream_t (passed as void*; NULL = the
+ *     default stream) and the call returns without waiting, except
+ *     fcp_queue_build which returns after its upload has completed.
+ *   - tensor layout is packed token-major: Q, O, dO, dQ [T_q, Hq, d];
+ *     K, V, dK, dV [T_kv, Hkv, d]; LSE, D [T_q, Hq]; row-major, no padding.
+ *     Q/K/V/dO are bf16; partial O, LSE, dQ/dK/dV are fp32; final O is bf16 or
+ *     fp32 (FCP_FLAG_O_F32).  Query head h reads KV head h * Hkv / Hq.
+ */
+#ifndef FCP_H_
+#define FCP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FCP_OK = 0,
+  FCP_ERR_INVALID_ARG = -1,      /* null pointer, negative size, owned block out of range ... */
+  FCP_ERR_BUFFER_TOO_SMALL = -2, /* a table capacity (or the workspace) is too small; needed counts are written back */
+  FCP_ERR_UNSUPPORTED = -3,      /* head_dim not in {64,128}, Hq % Hkv != 0, ... */
+  FCP_ERR_HIP = -4               /* a HIP call failed; see fcp_last_error() */
+} fcp_status;
+
+enum { FCP_KIND_FULL = 0, FCP_KIND_DIAG = 1 };
+
+/* One fixed-size block of one sequence (the paper's scheduling, compute and transfer unit). */
+typedef struct { int32_t seq, idx, tok_start, tok_len; } fcp_block;
+/* One work item of the dependency list: query block x KV block, FULL or causal-diagonal. */
+typedef struct { int32_t q_blk, kv_blk, kind, slot; } fcp_pair;
+/* One execution stage of a query block: up to c consecutive pairs -> one partial (O, LSE). */
+typedef struct { int32_t q_blk, pair_begin, n_pairs, row_start; } fcp_slot;
+
+enum {
+  FCP_FLAG_O_F32 = 1             /* fcp_merge_partials writes fp32 O instead of bf16 (bwd then reads fp32 O) */
+};
+
+/* Problem descriptor.  All table pointers are HOST pointers to tables produced by
+ * fcp_plan_blocks (or built by the caller to the same rules). */
+typedef struct {
+  int32_t n_q_heads, n_kv_heads, head_dim, block_size;
+  float   softmax_scale;         /* 0 -> 1/sqrt(head_dim) */
+  int32_t flags;
+  int32_t n_kv_blocks, n_q_blocks, n_pairs, n_slots, n_slot_rows;
+  const fcp_block* kv_blocks;
+  const fcp_block* q_blocks;
+  const fcp_pair*  pairs;
+  const fcp_slot*  slots;
+} fcp_problem;
+
+/*
+ * fcp_plan_blocks -- sharding policy G and the worker's dependency list (host, integer only).
+ *
+ * Paper: section "Block Distributor" (every sequence is cut into fixed-size blocks, more blocks
+ * for longer sequences; a sequence shorter than a block is one ragged block handled by the
+ * variable-length path); Zig-Zag figure caption (under a causal mask the i-th query block
+ * computes with KV blocks 0..i of its sequence); bottom-up coalescer (c sub-stages per stage).
+ *
+ * seq_lens[n_seqs]  host; length of every sequence whose KV is resident (>= 0; 0 -> no block).
+ * block_size > 0; causal 0/1; coalesce c >= 1, or 0 = all KV blocks of a query block in one slot.
+ * q_owned           host; n_q_owned rows of (seq, idx_in_seq), strictly increasing; NULL = the
+ *                   worker owns the query side of every block.
+ * Tables (host, caller-allocated): *n_x holds the capacity on entry and the count on return.
+ * A NULL table pointer makes the call a size query (counts only).  If a capacity is too small
+ * the counts are still written and FCP_ERR_BUFFER_TOO_SMALL is returned.
+ *   kv_blocks: all blocks by (seq, idx); tok_start = row in the K/V buffers.
+ *   q_blocks : owned blocks by (seq, idx); tok_start = row in the Q buffer (owned blocks packed).
+ *   pairs    : by (q_blk, kv_blk); causal -> FULL for j < i, DIAG for j == i; else FULL for all j.
+ *   slots    : the r-th pair of a query block belongs to its local slot r / c; slots are numbered
+ *              globally in pair order; slot rows [row_start, row_start + tok_len) of the partial
+ *              buffers belong to it.  *n_slot_rows = total rows of the partial buffers.
+ */
+int fcp_plan_blocks(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
+                    int32_t causal, int32_t coalesce,
+                    const int32_t* q_owned, int32_t n_q_owned,
+                    fcp_block* kv_blocks, int32_t* n_kv_blocks,
+                    fcp_block* q_blocks, int32_t* n_q_blocks,
+                    fcp_pair* pairs, int32_t* n_pairs,
+                    fcp_slot* slots, int32_t* n_slots,
+                    int32_t* n_slot_rows);
+
+/*
+ * fcp_workspace_bytes -- size of the device workspace that fcp_queue_build fills for `p`.
+ * Validates the descriptor (table consistency, supported shapes).
+ */
+int fcp_workspace_bytes(const fcp_problem* p, size_t* bytes);
+
+/*
+ * fcp_queue_build -- work-queue scheduler, host part.
+ *
+ * Paper analogue: the attention kernel is launched with a margin of idle units to dodge wave
+ * quantisation (section "Implementation"); here the pair list is expanded into weighted work
+ * items (forward: slot x query tile x query head; backward: KV tile x KV head with its list of
+ * dependent query blocks; merge: row ranges), ordered heavy-first and spread over the chip's
+ * eight XCD queues, which persistent workgroups drain through atomic counters.
+ *
+ * workspace: device, >= fcp_workspace_bytes, 256-byte aligned; owned by the caller, must stay
+ * untouched between this call and the last fwd/merge/bwd call that uses it.  Calls using one
+ * workspace must not overlap in time (they share its counters).  Synchronises `stream`.
+ */
+int fcp_queue_build(const fcp_problem* p, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fcp_block_attn_fwd -- partial attention of every slot (flash-style, online softmax).
+ *
+ * Paper: section "Attention Computation" (O = Softmax(Q K^T / sqrt(D), mask) V) restricted to
+ * the KV blocks of one stage; per-row log-sum-exp kept so that stages can be reduced later.
+ * For slot s of query block b, rows r < tok_len(b):
+ *   o_part [row_start(s) + r, h, :] = softmax over the slot's visible keys (normalised)
+ *   lse_part[row_start(s) + r, h]   = ln sum exp(scale * q.k) over those keys
+ * q [T_q,Hq,d], k, v [T_kv,Hkv,d]: device bf16.  o_part [n_slot_rows,Hq,d], lse_part
+ * [n_slot_rows,Hq]: device fp32, fully overwritten.  workspace: as built by fcp_queue_build.
+ */
+int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
+                       float* o_part, float* lse_part, void* workspace, void* stream);
+
+/*
+ * fcp_merge_partials -- reduce the partials of each query block to the final output.
+ *
+ * Paper: section "Context Parallelism" (intermediate results over slices are reduced to the
+ * final outputs).  LSE = ln sum_p exp(LSE_p); O = sum_p exp(LSE_p - LSE) O_p; exp(-inf) = 0;
+ * a row with only empty partials gets O = 0, LSE = -inf.
+ * o [T_q,Hq,d]: device, bf16 (default) or fp32 (FCP_FLAG_O_F32); lse [T_q,Hq]: device fp32.
+ */
+int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* lse_part,
+                       void* o, float* lse, void* workspace, void* stream);
+
+/*
+ * fcp_block_attn_bwd -- gradients of the worker's share.
+ *
+ * Paper: section "Attention Computation" states that the backward pass is implemented alongside
+ * the forward; this is the analytic gradient of the forward definition, recomputing P from the
+ * final LSE: D = rowsum(dO o O); P = exp(scale q.k - LSE); dV += P^T dO; dP = dO V^T;
+ * dS = P o (dP - D); dQ += scale dS K; dK += scale dS^T Q; dK/dV are summed over the query
+ * heads of a KV head and hold only the owned query rows' contribution.
+ * o: final O as written by fcp_merge_partials (dtype per flags); lse: final LSE; d_o bf16.
+ * dq [T_q,Hq,d], dk, dv [T_kv,Hkv,d]: device fp32, fully overwritten (zeroed on `stream`, then
+ * accumulated; the summation order of dq is not fixed, results may differ in the last bits
+ * between runs).
+ */
+int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
+                       const void* o, const float* lse, const void* d_o,
+                       float* dq, float* dk, float* dv, void* workspace, void* stream);
+
+/*
+ * The two halves of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
+ * fcp_bwd_preprocess: zeroes dq and writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
+ * fcp_block_attn_bwd_main: the contraction kernel; needs fcp_bwd_preprocess to have run on the
+ * same workspace (same stream, or ordered after it) with the same o / d_o / dq.
+ * Arguments, layouts and errors as for fcp_block_attn_bwd.
+ */
+int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o, float* dq,
+                       void* workspace, void* stream);
+int fcp_block_attn_bwd_main(const fcp_problem* p, const void* q, const void* k, const void* v,
+                            const float* lse, const void* d_o,
+                            float* dq, float* dk, float* dv, void* workspace, void* stream);
+
+/* Text of the calling thread's last error ("" if none).  The pointer stays valid until the
+ * thread's next failing call. */
+const char* fcp_last_error(void);
+
+/* Persistent grid sizes used by the kernels on the current device (for reports). */
+int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int32_t* bwd_grid);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FCP_H_ */

@@ -1,0 +1,187 @@
+"""ctypes binding of libfcp.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs inside the library's kernels.  Tensors may be
+anything exposing ``data_ptr()`` (PyTorch device tensors: PyTorch is used for
+device memory and streams only) or plain integers holding device addresses.
+There is no fallback: if the shared library is missing the import of this module
+fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfcp.so")
+
+FCP_OK = 0
+FCP_ERR_INVALID_ARG = -1
+FCP_ERR_BUFFER_TOO_SMALL = -2
+FCP_ERR_UNSUPPORTED = -3
+FCP_ERR_HIP = -4
+FCP_KIND_FULL, FCP_KIND_DIAG = 0, 1
+FCP_FLAG_O_F32 = 1
+
+EXPORTS = (
+    "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd",
+    "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_main",
+    "fcp_last_error", "fcp_device_info",
+)
+
+
+class FcpError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"fcp error {code}: {text}")
+        self.code = code
+
+
+class _Problem(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
+        ("softmax_scale", C.c_float), ("flags", C.c_int32),
+        ("n_kv_blocks", C.c_int32), ("n_q_blocks", C.c_int32), ("n_pairs", C.c_int32), ("n_slots", C.c_int32),
+        ("n_slot_rows", C.c_int32),
+        ("kv_blocks", C.c_void_p), ("q_blocks", C.c_void_p), ("pairs", C.c_void_p), ("slots", C.c_void_p),
+    ]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no CPU fallback.")
+    lib = C.CDLL(LIB_PATH)
+    i32p = C.POINTER(C.c_int32)
+    lib.fcp_plan_blocks.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32,
+                                    C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, i32p]
+    lib.fcp_workspace_bytes.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_size_t)]
+    lib.fcp_queue_build.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
+    lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
+    lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
+    lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
+    lib.fcp_block_attn_bwd_main.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 10
+    lib.fcp_last_error.restype = C.c_char_p
+    lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
+    for name in EXPORTS:
+        if name != "fcp_last_error":
+            getattr(lib, name).restype = C.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc):
+    if rc != FCP_OK:
+        raise FcpError(rc, _lib.fcp_last_error().decode())
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream        # torch.cuda.Stream
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def fcp_last_error() -> str:
+    return _lib.fcp_last_error().decode()
+
+
+def fcp_plan_blocks(seq_lens, block_size, causal=1, coalesce=0, q_owned=None):
+    """Returns dict(kv_blocks, q_blocks, pairs, slots: int32 [n,4]; n_slot_rows: int)."""
+    sl = _i32(np.asarray(seq_lens).reshape(-1))
+    qo = None if q_owned is None else _i32(np.asarray(q_owned).reshape(-1, 2))
+    i32p = C.POINTER(C.c_int32)
+    qo_p = None if qo is None else qo.ctypes.data_as(i32p)
+    n_qo = 0 if qo is None else len(qo)
+    counts = [C.c_int32(0) for _ in range(5)]
+    args = [sl.ctypes.data_as(i32p), len(sl), int(block_size), int(causal), int(coalesce), qo_p, n_qo]
+    _check(_lib.fcp_plan_blocks(*args, None, C.byref(counts[0]), None, C.byref(counts[1]), None,
+                                C.byref(counts[2]), None, C.byref(counts[3]), C.byref(counts[4])))
+    tabs = [np.zeros((max(1, c.value), 4), dtype=np.int32) for c in counts[:4]]
+    _check(_lib.fcp_plan_blocks(*args, tabs[0].ctypes.data, C.byref(counts[0]), tabs[1].ctypes.data,
+                                C.byref(counts[1]), tabs[2].ctypes.data, C.byref(counts[2]),
+                                tabs[3].ctypes.data, C.byref(counts[3]), C.byref(counts[4])))
+    tabs = [t[: c.value] for t, c in zip(tabs, counts[:4])]
+    return dict(kv_blocks=tabs[0], q_blocks=tabs[1], pairs=tabs[2], slots=tabs[3], n_slot_rows=counts[4].value)
+
+
+class Problem:
+    """Owns the host tables of an fcp_problem and the ctypes struct pointing at them."""
+
+    def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, block_size, softmax_scale=0.0, flags=0):
+        self.kv_blocks = _i32(plan["kv_blocks"]).reshape(-1, 4)
+        self.q_blocks = _i32(plan["q_blocks"]).reshape(-1, 4)
+        self.pairs = _i32(plan["pairs"]).reshape(-1, 4)
+        self.slots = _i32(plan["slots"]).reshape(-1, 4)
+        self.n_slot_rows = int(plan["n_slot_rows"])
+        self.n_q_heads, self.n_kv_heads, self.head_dim = int(n_q_heads), int(n_kv_heads), int(head_dim)
+        self.t_q = int(self.q_blocks[:, 3].sum()) if len(self.q_blocks) else 0
+        self.t_kv = int(self.kv_blocks[:, 3].sum()) if len(self.kv_blocks) else 0
+        self.c = _Problem(
+            self.n_q_heads, self.n_kv_heads, self.head_dim, int(block_size), float(softmax_scale), int(flags),
+            len(self.kv_blocks), len(self.q_blocks), len(self.pairs), len(self.slots), self.n_slot_rows,
+            self.kv_blocks.ctypes.data if len(self.kv_blocks) else None,
+            self.q_blocks.ctypes.data if len(self.q_blocks) else None,
+            self.pairs.ctypes.data if len(self.pairs) else None,
+            self.slots.ctypes.data if len(self.slots) else None)
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def fcp_workspace_bytes(problem: Problem) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.fcp_workspace_bytes(problem.ref, C.byref(n)))
+    return n.value
+
+
+def fcp_queue_build(problem: Problem, workspace, workspace_bytes, stream=None):
+    _check(_lib.fcp_queue_build(problem.ref, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def fcp_block_attn_fwd(problem: Problem, q, k, v, o_part, lse_part, workspace, stream=None):
+    _check(_lib.fcp_block_attn_fwd(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o_part), _ptr(lse_part),
+                                   _ptr(workspace), _stream(stream)))
+
+
+def fcp_merge_partials(problem: Problem, o_part, lse_part, o, lse, workspace, stream=None):
+    _check(_lib.fcp_merge_partials(problem.ref, _ptr(o_part), _ptr(lse_part), _ptr(o), _ptr(lse),
+                                   _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_bwd(problem: Problem, q, k, v, o, lse, d_o, dq, dk, dv, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                   _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
+
+
+def fcp_bwd_preprocess(problem: Problem, o, d_o, dq, workspace, stream=None):
+    _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(d_o), _ptr(dq), _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_bwd_main(problem: Problem, q, k, v, lse, d_o, dq, dk, dv, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_main(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
+                                        _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
+
+
+def fcp_device_info():
+    a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(_lib.fcp_device_info(C.byref(a), C.byref(b), C.byref(c)))
+    return dict(n_compute_units=a.value, fwd_grid=b.value, bwd_grid=c.value)

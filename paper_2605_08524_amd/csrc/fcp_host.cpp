@@ -1,0 +1,413 @@
+// Host side of the library: block planner, descriptor validation, work-queue scheduler.
+// Integer work only; the only HIP calls are the workspace upload in fcp_queue_build.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "fcp_internal.h"
+
+namespace fcp {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int validate_problem(const fcp_problem* p) {
+  if (!p) { set_error("problem descriptor is NULL"); return FCP_ERR_INVALID_ARG; }
+  if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->block_size <= 0) {
+    set_error("heads and block_size must be positive"); return FCP_ERR_INVALID_ARG;
+  }
+  if (p->head_dim != 64 && p->head_dim != 128) {
+    set_error("head_dim %d unsupported (64 or 128)", p->head_dim); return FCP_ERR_UNSUPPORTED;
+  }
+  if (p->n_q_heads % p->n_kv_heads != 0) {
+    set_error("n_q_heads %d is not a multiple of n_kv_heads %d", p->n_q_heads, p->n_kv_heads);
+    return FCP_ERR_UNSUPPORTED;
+  }
+  if (p->n_kv_blocks < 0 || p->n_q_blocks < 0 || p->n_pairs < 0 || p->n_slots < 0 || p->n_slot_rows < 0) {
+    set_error("negative table count"); return FCP_ERR_INVALID_ARG;
+  }
+  if ((p->n_kv_blocks && !p->kv_blocks) || (p->n_q_blocks && !p->q_blocks) || (p->n_pairs && !p->pairs) ||
+      (p->n_slots && !p->slots)) {
+    set_error("NULL table with a non-zero count"); return FCP_ERR_INVALID_ARG;
+  }
+  if (!(p->softmax_scale >= 0.0f)) { set_error("softmax_scale must be >= 0 (0 = 1/sqrt(d))"); return FCP_ERR_INVALID_ARG; }
+  int64_t tok = 0;
+  for (int i = 0; i < p->n_kv_blocks; i++) {
+    const fcp_block& b = p->kv_blocks[i];
+    if (b.tok_len <= 0 || b.tok_len > p->block_size || b.tok_start != tok) {
+      set_error("kv_blocks[%d]: tok_len/tok_start inconsistent (blocks must be packed in order)", i);
+      return FCP_ERR_INVALID_ARG;
+    }
+    tok += b.tok_len;
+    if (tok > INT32_MAX) { set_error("more than 2^31-1 KV tokens"); return FCP_ERR_UNSUPPORTED; }
+  }
+  tok = 0;
+  for (int i = 0; i < p->n_q_blocks; i++) {
+    const fcp_block& b = p->q_blocks[i];
+    if (b.tok_len <= 0 || b.tok_len > p->block_size || b.tok_start != tok) {
+      set_error("q_blocks[%d]: tok_len/tok_start inconsistent (blocks must be packed in order)", i);
+      return FCP_ERR_INVALID_ARG;
+    }
+    tok += b.tok_len;
+  }
+  int prev_q = -1;
+  int64_t pair_cursor = 0;
+  for (int s = 0; s < p->n_slots; s++) {
+    const fcp_slot& sl = p->slots[s];
+    if (sl.q_blk < 0 || sl.q_blk >= p->n_q_blocks || sl.q_blk < prev_q) {
+      set_error("slots[%d]: q_blk out of range or not ascending", s); return FCP_ERR_INVALID_ARG;
+    }
+    prev_q = sl.q_blk;
+    if (sl.pair_begin != pair_cursor || sl.n_pairs < 0 || pair_cursor + sl.n_pairs > p->n_pairs) {
+      set_error("slots[%d]: pair range must continue where the previous slot ended", s);
+      return FCP_ERR_INVALID_ARG;
+    }
+    pair_cursor += sl.n_pairs;
+    const int qlen = p->q_blocks[sl.q_blk].tok_len;
+    if (sl.row_start < 0 || (int64_t)sl.row_start + qlen > p->n_slot_rows) {
+      set_error("slots[%d]: rows outside the partial buffers", s); return FCP_ERR_INVALID_ARG;
+    }
+    for (int64_t i = sl.pair_begin; i < sl.pair_begin + sl.n_pairs; i++) {
+      const fcp_pair& pr = p->pairs[i];
+      if (pr.q_blk != sl.q_blk || pr.slot != s || pr.kv_blk < 0 || pr.kv_blk >= p->n_kv_blocks ||
+          (pr.kind != FCP_KIND_FULL && pr.kind != FCP_KIND_DIAG)) {
+        set_error("pairs[%lld]: inconsistent with slot %d", (long long)i, s); return FCP_ERR_INVALID_ARG;
+      }
+      if (pr.kind == FCP_KIND_DIAG) {
+        const fcp_block& qb = p->q_blocks[pr.q_blk];
+        const fcp_block& kb = p->kv_blocks[pr.kv_blk];
+        if (qb.seq != kb.seq || qb.idx != kb.idx || qb.tok_len != kb.tok_len) {
+          set_error("pairs[%lld]: a DIAG pair must join a block with itself", (long long)i);
+          return FCP_ERR_INVALID_ARG;
+        }
+      }
+    }
+  }
+  if (pair_cursor != p->n_pairs) { set_error("slots do not cover all pairs"); return FCP_ERR_INVALID_ARG; }
+  return FCP_OK;
+}
+
+int compute_layout(const fcp_problem* p, WsLayout* L) {
+  std::memset(L, 0, sizeof(*L));
+  for (int s = 0; s < p->n_slots; s++)
+    L->n_fwd_items += ceil_div(p->q_blocks[p->slots[s].q_blk].tok_len, kFwdTileM) * p->n_q_heads;
+  for (int b = 0; b < p->n_kv_blocks; b++)
+    L->n_bwd_items += ceil_div(p->kv_blocks[b].tok_len, kBwdTileN) * p->n_kv_heads;
+  L->n_bwd_deps = p->n_pairs;
+  for (int b = 0; b < p->n_q_blocks; b++) {
+    L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
+    L->t_q += p->q_blocks[b].tok_len;
+  }
+  for (int b = 0; b < p->n_kv_blocks; b++) L->t_kv += p->kv_blocks[b].tok_len;
+  if (L->t_q * p->n_q_heads > INT32_MAX) { set_error("more than 2^31-1 (query row, head) entries"); return FCP_ERR_UNSUPPORTED; }
+  if (L->n_fwd_items > INT32_MAX || L->n_bwd_items > INT32_MAX || L->n_merge_items > INT32_MAX) {
+    set_error("too many work items"); return FCP_ERR_UNSUPPORTED;
+  }
+  auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  size_t off = align(sizeof(WsHeader));
+  L->off_pairs = off;       off = align(off + sizeof(DevPair) * (size_t)std::max(1, p->n_pairs));
+  L->off_fwd_items = off;   off = align(off + sizeof(FwdItem) * (size_t)std::max<int64_t>(1, L->n_fwd_items));
+  L->off_bwd_deps = off;    off = align(off + sizeof(BwdDep) * (size_t)std::max<int64_t>(1, L->n_bwd_deps));
+  L->off_bwd_items = off;   off = align(off + sizeof(BwdItem) * (size_t)std::max<int64_t>(1, L->n_bwd_items));
+  L->off_merge_items = off; off = align(off + sizeof(MergeItem) * (size_t)std::max<int64_t>(1, L->n_merge_items));
+  L->off_slot_rh = off;     off = align(off + sizeof(int32_t) * (size_t)std::max(1, p->n_slots));
+  L->off_delta = off;       off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
+  L->total = off;
+  return FCP_OK;
+}
+
+namespace {
+
+// Longest-processing-time assignment of weighted groups to the XCD queues: groups in
+// descending weight, each to the currently lightest queue.  Ties resolve to the lower index.
+template <class Item>
+void spread_over_xcds(std::vector<std::vector<Item>>& groups, std::vector<int64_t>& weight,
+                      std::vector<Item>* out, int32_t begin[kNumXcd + 1]) {
+  std::vector<int> order(groups.size());
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return weight[a] > weight[b]; });
+  std::vector<std::vector<int>> per_xcd(kNumXcd);
+  int64_t load[kNumXcd] = {0};
+  for (int g : order) {
+    int best = 0;
+    for (int x = 1; x < kNumXcd; x++)
+      if (load[x] < load[best]) best = x;
+    per_xcd[best].push_back(g);
+    load[best] += weight[g];
+  }
+  out->clear();
+  for (int x = 0; x < kNumXcd; x++) {
+    begin[x] = (int32_t)out->size();
+    for (int g : per_xcd[x])
+      for (const Item& it : groups[g]) out->push_back(it);
+  }
+  begin[kNumXcd] = (int32_t)out->size();
+}
+
+}  // namespace
+}  // namespace fcp
+
+using namespace fcp;
+
+extern "C" const char* fcp_last_error(void) { return g_err; }
+
+extern "C" int fcp_plan_blocks(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
+                               int32_t causal, int32_t coalesce,
+                               const int32_t* q_owned, int32_t n_q_owned,
+                               fcp_block* kv_blocks, int32_t* n_kv_blocks,
+                               fcp_block* q_blocks, int32_t* n_q_blocks,
+                               fcp_pair* pairs, int32_t* n_pairs,
+                               fcp_slot* slots, int32_t* n_slots,
+                               int32_t* n_slot_rows) {
+  if (n_seqs < 0 || (n_seqs > 0 && !seq_lens) || block_size <= 0 || coalesce < 0 || n_q_owned < 0 ||
+      !n_kv_blocks || !n_q_blocks || !n_pairs || !n_slots || !n_slot_rows) {
+    set_error("fcp_plan_blocks: invalid argument"); return FCP_ERR_INVALID_ARG;
+  }
+  // Pass 1: per-sequence block counts and offsets.
+  std::vector<int64_t> first_blk(n_seqs + 1, 0), tok_off(n_seqs + 1, 0);
+  for (int s = 0; s < n_seqs; s++) {
+    if (seq_lens[s] < 0) { set_error("fcp_plan_blocks: seq_lens[%d] < 0", s); return FCP_ERR_INVALID_ARG; }
+    first_blk[s + 1] = first_blk[s] + ceil_div(seq_lens[s], block_size);
+    tok_off[s + 1] = tok_off[s] + seq_lens[s];
+  }
+  if (tok_off[n_seqs] > INT32_MAX || first_blk[n_seqs] > INT32_MAX) {
+    set_error("fcp_plan_blocks: more than 2^31-1 tokens or blocks"); return FCP_ERR_UNSUPPORTED;
+  }
+  auto nblk = [&](int s) { return (int32_t)(first_blk[s + 1] - first_blk[s]); };
+  auto blk_len = [&](int s, int i) { return std::min<int32_t>(block_size, seq_lens[s] - i * block_size); };
+  const int64_t need_kv = first_blk[n_seqs];
+  // Owned query blocks.
+  const bool all_owned = (q_owned == nullptr);
+  if (!all_owned) {
+    for (int t = 0; t < n_q_owned; t++) {
+      const int32_t s = q_owned[2 * t], i = q_owned[2 * t + 1];
+      if (s < 0 || s >= n_seqs || i < 0 || i >= nblk(s)) {
+        set_error("fcp_plan_blocks: q_owned[%d] = (%d, %d) out of range", t, s, i); return FCP_ERR_INVALID_ARG;
+      }
+      if (t > 0) {
+        const int32_t ps = q_owned[2 * t - 2], pi = q_owned[2 * t - 1];
+        if (ps > s || (ps == s && pi >= i)) {
+          set_error("fcp_plan_blocks: q_owned must be strictly increasing in (seq, idx)");
+          return FCP_ERR_INVALID_ARG;
+        }
+      }
+    }
+  }
+  const int64_t need_q = all_owned ? need_kv : n_q_owned;
+  // Pass 2: counts of pairs, slots, partial rows.
+  int64_t need_pairs = 0, need_slots = 0, need_rows = 0;
+  auto for_each_owned = [&](auto&& fn) {
+    if (all_owned) {
+      for (int s = 0; s < n_seqs; s++)
+        for (int i = 0; i < nblk(s); i++) fn(s, i);
+    } else {
+      for (int t = 0; t < n_q_owned; t++) fn(q_owned[2 * t], q_owned[2 * t + 1]);
+    }
+  };
+  for_each_owned([&](int s, int i) {
+    const int64_t np = causal ? (i + 1) : nblk(s);
+    const int64_t ns = coalesce == 0 ? 1 : ceil_div(np, coalesce);
+    need_pairs += np;
+    need_slots += ns;
+    need_rows += ns * blk_len(s, i);
+  });
+  if (need_pairs > INT32_MAX || need_rows > INT32_MAX) {
+    set_error("fcp_plan_blocks: more than 2^31-1 pairs or partial rows"); return FCP_ERR_UNSUPPORTED;
+  }
+  const int32_t cap_kv = *n_kv_blocks, cap_q = *n_q_blocks, cap_p = *n_pairs, cap_s = *n_slots;
+  *n_kv_blocks = (int32_t)need_kv; *n_q_blocks = (int32_t)need_q; *n_pairs = (int32_t)need_pairs;
+  *n_slots = (int32_t)need_slots; *n_slot_rows = (int32_t)need_rows;
+  if (!kv_blocks && !q_blocks && !pairs && !slots) return FCP_OK;   // size query
+  if (!kv_blocks || !q_blocks || !pairs || !slots) {
+    set_error("fcp_plan_blocks: pass all four tables or none"); return FCP_ERR_INVALID_ARG;
+  }
+  if (cap_kv < need_kv || cap_q < need_q || cap_p < need_pairs || cap_s < need_slots) {
+    set_error("fcp_plan_blocks: table capacity too small (need %lld kv, %lld q, %lld pairs, %lld slots)",
+              (long long)need_kv, (long long)need_q, (long long)need_pairs, (long long)need_slots);
+    return FCP_ERR_BUFFER_TOO_SMALL;
+  }
+  // Pass 3: fill.
+  for (int s = 0; s < n_seqs; s++)
+    for (int i = 0; i < nblk(s); i++)
+      kv_blocks[first_blk[s] + i] = {s, i, (int32_t)(tok_off[s] + (int64_t)i * block_size), blk_len(s, i)};
+  int32_t qb = 0, qtok = 0, np_out = 0, ns_out = 0, row = 0;
+  for_each_owned([&](int s, int i) {
+    const int32_t len = blk_len(s, i);
+    q_blocks[qb] = {s, i, qtok, len};
+    qtok += len;
+    const int32_t np = causal ? (i + 1) : nblk(s);
+    for (int32_t r = 0; r < np; r++) {
+      const bool opens = (coalesce == 0) ? (r == 0) : (r % coalesce == 0);
+      if (opens) {
+        slots[ns_out] = {qb, np_out, 0, row};
+        ns_out++;
+        row += len;
+      }
+      const int32_t kind = (causal && r == i) ? FCP_KIND_DIAG : FCP_KIND_FULL;
+      pairs[np_out] = {qb, (int32_t)(first_blk[s] + r), kind, ns_out - 1};
+      slots[ns_out - 1].n_pairs++;
+      np_out++;
+    }
+    qb++;
+  });
+  return FCP_OK;
+}
+
+extern "C" int fcp_workspace_bytes(const fcp_problem* p, size_t* bytes) {
+  if (!bytes) { set_error("fcp_workspace_bytes: bytes is NULL"); return FCP_ERR_INVALID_ARG; }
+  int rc = validate_problem(p);
+  if (rc) return rc;
+  WsLayout L;
+  rc = compute_layout(p, &L);
+  if (rc) return rc;
+  *bytes = L.total;
+  return FCP_OK;
+}
+
+extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_problem(p);
+  if (rc) return rc;
+  WsLayout L;
+  rc = compute_layout(p, &L);
+  if (rc) return rc;
+  if (!workspace || ((uintptr_t)workspace & 255)) {
+    set_error("fcp_queue_build: workspace is NULL or not 256-byte aligned"); return FCP_ERR_INVALID_ARG;
+  }
+  if (workspace_bytes < L.total) {
+    set_error("fcp_queue_build: workspace too small (%zu < %zu)", workspace_bytes, L.total);
+    return FCP_ERR_BUFFER_TOO_SMALL;
+  }
+  const size_t upload = L.off_delta;   // everything before the D scratch region
+  std::vector<unsigned char> host(upload, 0);
+  WsHeader* hdr = reinterpret_cast<WsHeader*>(host.data());
+  DevPair* dpairs = reinterpret_cast<DevPair*>(host.data() + L.off_pairs);
+  for (int i = 0; i < p->n_pairs; i++) {
+    const fcp_block& kb = p->kv_blocks[p->pairs[i].kv_blk];
+    dpairs[i] = {kb.tok_start, kb.tok_len, p->pairs[i].kind, 0};
+  }
+  const int G = p->n_q_heads / p->n_kv_heads;
+  // ---- forward: one group per (slot, KV head): its query tiles x the G query heads share K/V.
+  {
+    std::vector<std::vector<FwdItem>> groups;
+    std::vector<int64_t> weight;
+    groups.reserve((size_t)p->n_slots * p->n_kv_heads);
+    for (int s = 0; s < p->n_slots; s++) {
+      const fcp_slot& sl = p->slots[s];
+      const fcp_block& qb = p->q_blocks[sl.q_blk];
+      const int n_tiles = (int)ceil_div(qb.tok_len, kFwdTileM);
+      std::vector<int64_t> tile_w(n_tiles, 0);
+      for (int t = n_tiles - 1; t >= 0; t--) {
+        const int off = t * kFwdTileM;
+        const int rows = std::min(kFwdTileM, qb.tok_len - off);
+        for (int i = sl.pair_begin; i < sl.pair_begin + sl.n_pairs; i++) {
+          const int kvlen = dpairs[i].kv_len;
+          const int cols = dpairs[i].kind == FCP_KIND_DIAG ? std::min(kvlen, off + rows) : kvlen;
+          tile_w[t] += (int64_t)rows * cols;
+        }
+      }
+      for (int g = 0; g < p->n_kv_heads; g++) {
+        std::vector<FwdItem> items;
+        int64_t w = 0;
+        for (int t = n_tiles - 1; t >= 0; t--) {       // later tiles of a DIAG pair are heavier
+          const int off = t * kFwdTileM;
+          const int rows = std::min(kFwdTileM, qb.tok_len - off);
+          for (int hh = 0; hh < G; hh++) {
+            items.push_back({qb.tok_start + off, rows, sl.row_start + off, off, sl.pair_begin, sl.n_pairs,
+                             g * G + hh, 0});
+            w += tile_w[t];
+          }
+        }
+        groups.push_back(std::move(items));
+        weight.push_back(w);
+      }
+    }
+    std::vector<FwdItem> flat;
+    spread_over_xcds(groups, weight, &flat, hdr->fwd_begin);
+    if ((int64_t)flat.size() != L.n_fwd_items) { set_error("internal: forward item count mismatch"); return FCP_ERR_INVALID_ARG; }
+    if (!flat.empty()) std::memcpy(host.data() + L.off_fwd_items, flat.data(), flat.size() * sizeof(FwdItem));
+  }
+  // ---- backward: dependency lists per KV block, one group per (KV block, KV head).
+  {
+    std::vector<int32_t> dep_count(p->n_kv_blocks + 1, 0);
+    for (int i = 0; i < p->n_pairs; i++) dep_count[p->pairs[i].kv_blk + 1]++;
+    for (int b = 0; b < p->n_kv_blocks; b++) dep_count[b + 1] += dep_count[b];
+    std::vector<int32_t> cursor(dep_count.begin(), dep_count.end() - 1);
+    BwdDep* deps = reinterpret_cast<BwdDep*>(host.data() + L.off_bwd_deps);
+    for (int i = 0; i < p->n_pairs; i++) {           // pairs are visited in q order -> deps ascend in q
+      const fcp_block& qb = p->q_blocks[p->pairs[i].q_blk];
+      deps[cursor[p->pairs[i].kv_blk]++] = {qb.tok_start, qb.tok_len, p->pairs[i].kind, 0};
+    }
+    std::vector<std::vector<BwdItem>> groups;
+    std::vector<int64_t> weight;
+    groups.reserve((size_t)p->n_kv_blocks * p->n_kv_heads);
+    for (int b = 0; b < p->n_kv_blocks; b++) {
+      const fcp_block& kb = p->kv_blocks[b];
+      const int n_tiles = (int)ceil_div(kb.tok_len, kBwdTileN);
+      const int d0 = dep_count[b], nd = dep_count[b + 1] - dep_count[b];
+      std::vector<int64_t> tile_w(n_tiles, 0);
+      for (int t = 0; t < n_tiles; t++) {
+        const int off = t * kBwdTileN;
+        const int rows = std::min(kBwdTileN, kb.tok_len - off);
+        for (int i = d0; i < d0 + nd; i++) {
+          const int qrows = deps[i].kind == FCP_KIND_DIAG ? std::max(0, deps[i].q_len - off) : deps[i].q_len;
+          tile_w[t] += (int64_t)rows * qrows * G;
+        }
+      }
+      for (int g = 0; g < p->n_kv_heads; g++) {
+        std::vector<BwdItem> items;
+        int64_t w = 0;
+        for (int t = 0; t < n_tiles; t++) {            // earlier tiles of a DIAG pair are heavier
+          const int off = t * kBwdTileN;
+          items.push_back({kb.tok_start + off, std::min(kBwdTileN, kb.tok_len - off), off, d0, nd, g, 0, 0});
+          w += tile_w[t];
+        }
+        groups.push_back(std::move(items));
+        weight.push_back(w);
+      }
+    }
+    std::vector<BwdItem> flat;
+    spread_over_xcds(groups, weight, &flat, hdr->bwd_begin);
+    if ((int64_t)flat.size() != L.n_bwd_items) { set_error("internal: backward item count mismatch"); return FCP_ERR_INVALID_ARG; }
+    if (!flat.empty()) std::memcpy(host.data() + L.off_bwd_items, flat.data(), flat.size() * sizeof(BwdItem));
+  }
+  // ---- merge: row-head chunks per query block; slots of a query block are consecutive.
+  {
+    std::vector<int32_t> slot_begin(p->n_q_blocks + 1, 0);
+    for (int s = 0; s < p->n_slots; s++) slot_begin[p->slots[s].q_blk + 1]++;
+    for (int b = 0; b < p->n_q_blocks; b++) slot_begin[b + 1] += slot_begin[b];
+    int32_t* slot_rh = reinterpret_cast<int32_t*>(host.data() + L.off_slot_rh);
+    for (int s = 0; s < p->n_slots; s++) {
+      const int64_t rh = (int64_t)p->slots[s].row_start * p->n_q_heads;
+      if (rh > INT32_MAX) { set_error("partial buffers exceed 2^31-1 (row, head) entries"); return FCP_ERR_UNSUPPORTED; }
+      slot_rh[s] = (int32_t)rh;
+    }
+    MergeItem* mi = reinterpret_cast<MergeItem*>(host.data() + L.off_merge_items);
+    int64_t n = 0;
+    for (int b = 0; b < p->n_q_blocks; b++) {
+      const fcp_block& qb = p->q_blocks[b];
+      const int64_t total = (int64_t)qb.tok_len * p->n_q_heads;
+      for (int64_t off = 0; off < total; off += kMergeChunk) {
+        mi[n++] = {(int32_t)((int64_t)qb.tok_start * p->n_q_heads + off), (int32_t)std::min<int64_t>(kMergeChunk, total - off),
+                   slot_begin[b], slot_begin[b + 1] - slot_begin[b], (int32_t)off, 0, 0, 0};
+      }
+    }
+    if (n != L.n_merge_items) { set_error("internal: merge item count mismatch"); return FCP_ERR_INVALID_ARG; }
+  }
+  hipError_t e = hipMemcpyAsync(workspace, host.data(), upload, hipMemcpyHostToDevice, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) { set_error("fcp_queue_build: %s", hipGetErrorString(e)); return FCP_ERR_HIP; }
+  return FCP_OK;
+}

@@ -1,0 +1,47 @@
+// Internal layout shared by the host scheduler and the HIP kernels (not part of the ABI).
+#ifndef FCP_INTERNAL_H_
+#define FCP_INTERNAL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fcp.h"
+
+namespace fcp {
+
+constexpr int kNumXcd = 8;          // MI355X: 8 XCDs, each with its own L2; workgroup b runs on XCD b % 8
+constexpr int kFwdTileM = 128;      // query rows per forward work item (4 waves x 32 rows)
+constexpr int kBwdTileN = 128;      // KV rows per backward work item (4 waves x 32 rows)
+constexpr int kMergeChunk = 1024;   // (row, head) entries per merge work item
+
+// Device-side records (all int32 so the host can build them as plain arrays).
+struct DevPair { int32_t kv_start, kv_len, kind, pad; };
+struct FwdItem { int32_t q_start, q_rows, out_row, tile_off, pair_begin, n_pairs, head, pad; };
+struct BwdDep  { int32_t q_start, q_len, kind, pad; };
+struct BwdItem { int32_t kv_start, kv_rows, tile_off, dep_begin, n_deps, kv_head, pad0, pad1; };
+struct MergeItem { int32_t out_rh, n_rh, slot_begin, n_slots, rh_off, pad0, pad1, pad2; };
+
+// Header at the start of the workspace.  Counters are zero between launches: the last
+// workgroup of a persistent launch to run dry clears the ones it used.
+struct WsHeader {
+  int32_t fwd_counter[kNumXcd];
+  int32_t bwd_counter[kNumXcd];
+  int32_t fwd_done, bwd_done, pad0[6];
+  int32_t fwd_begin[kNumXcd + 1];   // item range of each XCD queue
+  int32_t pad1[7];
+  int32_t bwd_begin[kNumXcd + 1];
+  int32_t pad2[7];
+};
+
+// Byte offsets of the workspace sections, a pure function of the problem's counts.
+struct WsLayout {
+  int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, t_q, t_kv;
+  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_delta, total;
+};
+
+int validate_problem(const fcp_problem* p);           // host; sets the error text
+int compute_layout(const fcp_problem* p, WsLayout* L); // host
+void set_error(const char* fmt, ...);
+
+}  // namespace fcp
+#endif

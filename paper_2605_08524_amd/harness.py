@@ -1,0 +1,81 @@
+"""Device-side plumbing shared by the tests, the smoke check and the benchmark: uploads a
+workload's tensors with PyTorch, allocates outputs and the workspace, and calls the C ABI.
+No arithmetic of the method happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def to_dev_bf16(bits: np.ndarray, device) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on `device` (bit-exact)."""
+    t = torch.from_numpy(bits.view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+class DevicePath:
+    """Holds the device buffers of one workload and runs the path's calls on them."""
+
+    def __init__(self, wl, device, flags=0, backward=False, stream=None):
+        self.wl, self.device, self.stream = wl, device, stream
+        self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+        self.problem = B.Problem(self.plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, 0.0, flags)
+        p = self.problem
+        Hq, Hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+        self.q = to_dev_bf16(wl.q(), device)
+        self.k = to_dev_bf16(wl.k(), device)
+        self.v = to_dev_bf16(wl.v(), device)
+        f32 = dict(dtype=torch.float32, device=device)
+        nan = float("nan")
+        self.o_part = torch.full((max(1, p.n_slot_rows), Hq, d), nan, **f32)
+        self.lse_part = torch.full((max(1, p.n_slot_rows), Hq), nan, **f32)
+        o_dtype = torch.float32 if (flags & B.FCP_FLAG_O_F32) else torch.bfloat16
+        self.o = torch.full((max(1, p.t_q), Hq, d), nan, dtype=o_dtype, device=device)
+        self.lse = torch.full((max(1, p.t_q), Hq), nan, **f32)
+        self.ws_bytes = B.fcp_workspace_bytes(p)
+        self.ws = torch.zeros(self.ws_bytes + 256, dtype=torch.uint8, device=device)
+        off = (-self.ws.data_ptr()) % 256
+        self.ws_ptr = self.ws.data_ptr() + off
+        B.fcp_queue_build(p, self.ws_ptr, self.ws_bytes, stream)
+        if backward:
+            self.d_o = to_dev_bf16(wl.d_o(), device)
+            self.dq = torch.full((max(1, p.t_q), Hq, d), nan, **f32)
+            self.dk = torch.full((max(1, p.t_kv), Hkv, d), nan, **f32)
+            self.dv = torch.full((max(1, p.t_kv), Hkv, d), nan, **f32)
+
+    def fwd(self):
+        B.fcp_block_attn_fwd(self.problem, self.q, self.k, self.v, self.o_part, self.lse_part, self.ws_ptr, self.stream)
+
+    def merge(self):
+        B.fcp_merge_partials(self.problem, self.o_part, self.lse_part, self.o, self.lse, self.ws_ptr, self.stream)
+
+    def bwd(self):
+        B.fcp_block_attn_bwd(self.problem, self.q, self.k, self.v, self.o, self.lse, self.d_o,
+                             self.dq, self.dk, self.dv, self.ws_ptr, self.stream)
+
+
+    def bwd_pre(self):
+        B.fcp_bwd_preprocess(self.problem, self.o, self.d_o, self.dq, self.ws_ptr, self.stream)
+
+    def bwd_main(self):
+        B.fcp_block_attn_bwd_main(self.problem, self.q, self.k, self.v, self.lse, self.d_o,
+                                  self.dq, self.dk, self.dv, self.ws_ptr, self.stream)
+
+
+def run_path(wl, device, backward=False, flags=0):
+    """One pass of the whole path; returns host copies (numpy) of every output."""
+    dp = DevicePath(wl, device, flags=flags, backward=backward)
+    dp.fwd()
+    dp.merge()
+    if backward:
+        dp.bwd()
+    torch.cuda.synchronize(device)
+    p = dp.problem
+    out = dict(plan=dp.plan, o_part=dp.o_part[: p.n_slot_rows].cpu().numpy(),
+               lse_part=dp.lse_part[: p.n_slot_rows].cpu().numpy(),
+               o=dp.o[: p.t_q].float().cpu().numpy(), lse=dp.lse[: p.t_q].cpu().numpy())
+    if backward:
+        out.update(dq=dp.dq[: p.t_q].cpu().numpy(), dk=dp.dk[: p.t_kv].cpu().numpy(), dv=dp.dv[: p.t_kv].cpu().numpy())
+    return out
