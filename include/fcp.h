@@ -112,7 +112,7 @@ int fcp_workspace_bytes(const fcp_problem* p, size_t* bytes);
  * Paper analogue: the attention kernel is launched with a margin of idle units to dodge wave
  * quantisation (section "Implementation"); here the pair list is expanded into weighted work
  * items (forward: slot x query tile x query head; backward: KV tile x KV head with its list of
- * dependent query blocks; merge: row ranges), ordered heavy-first and spread over the chip's
+ * dependent query blocks for dK/dV, query block x tile x head for dQ; merge: row ranges), ordered heavy-first and spread over the chip's
  * eight XCD queues, which persistent workgroups drain through atomic counters.
  *
  * workspace: device, >= fcp_workspace_bytes, 256-byte aligned; owned by the caller, must stay
@@ -155,9 +155,8 @@ int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* l
  * dS = P o (dP - D); dQ += scale dS K; dK += scale dS^T Q; dK/dV are summed over the query
  * heads of a KV head and hold only the owned query rows' contribution.
  * o: final O as written by fcp_merge_partials (dtype per flags); lse: final LSE; d_o bf16.
- * dq [T_q,Hq,d], dk, dv [T_kv,Hkv,d]: device fp32, fully overwritten (zeroed on `stream`, then
- * accumulated; the summation order of dq is not fixed, results may differ in the last bits
- * between runs).
+ * dq [T_q,Hq,d], dk, dv [T_kv,Hkv,d]: device fp32, fully overwritten; every row has exactly one
+ * writer and a fixed summation order, so results are bit-reproducible from run to run.
  */
 int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
                        const void* o, const float* lse, const void* d_o,
@@ -165,12 +164,13 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
 
 /*
  * The two halves of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
- * fcp_bwd_preprocess: zeroes dq and writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
- * fcp_block_attn_bwd_main: the contraction kernel; needs fcp_bwd_preprocess to have run on the
- * same workspace (same stream, or ordered after it) with the same o / d_o / dq.
+ * fcp_bwd_preprocess: writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
+ * fcp_block_attn_bwd_main: the contraction kernels (dK/dV KV-stationary, dQ query-stationary);
+ * needs fcp_bwd_preprocess to have run on the same workspace (same stream, or ordered after it)
+ * with the same o / d_o.
  * Arguments, layouts and errors as for fcp_block_attn_bwd.
  */
-int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o, float* dq,
+int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o,
                        void* workspace, void* stream);
 int fcp_block_attn_bwd_main(const fcp_problem* p, const void* q, const void* k, const void* v,
                             const float* lse, const void* d_o,

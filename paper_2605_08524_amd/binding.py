@@ -61,7 +61,7 @@ def _load():
     lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
-    lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
+    lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 4
     lib.fcp_block_attn_bwd_main.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 10
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
@@ -172,8 +172,8 @@ def fcp_block_attn_bwd(problem: Problem, q, k, v, o, lse, d_o, dq, dk, dv, works
                                    _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
 
 
-def fcp_bwd_preprocess(problem: Problem, o, d_o, dq, workspace, stream=None):
-    _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(d_o), _ptr(dq), _ptr(workspace), _stream(stream)))
+def fcp_bwd_preprocess(problem: Problem, o, d_o, workspace, stream=None):
+    _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(d_o), _ptr(workspace), _stream(stream)))
 
 
 def fcp_block_attn_bwd_main(problem: Problem, q, k, v, lse, d_o, dq, dk, dv, workspace, stream=None):

@@ -102,13 +102,15 @@ int validate_problem(const fcp_problem* p) {
 
 int compute_layout(const fcp_problem* p, WsLayout* L) {
   std::memset(L, 0, sizeof(*L));
+  L->fwd_tile_m = kFwdTileM;
   for (int s = 0; s < p->n_slots; s++)
-    L->n_fwd_items += ceil_div(p->q_blocks[p->slots[s].q_blk].tok_len, kFwdTileM) * p->n_q_heads;
+    L->n_fwd_items += ceil_div(p->q_blocks[p->slots[s].q_blk].tok_len, L->fwd_tile_m) * p->n_q_heads;
   for (int b = 0; b < p->n_kv_blocks; b++)
     L->n_bwd_items += ceil_div(p->kv_blocks[b].tok_len, kBwdTileN) * p->n_kv_heads;
   L->n_bwd_deps = p->n_pairs;
   for (int b = 0; b < p->n_q_blocks; b++) {
     L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
+    L->n_dq_items += ceil_div(p->q_blocks[b].tok_len, kFwdTileM) * p->n_q_heads;
     L->t_q += p->q_blocks[b].tok_len;
   }
   for (int b = 0; b < p->n_kv_blocks; b++) L->t_kv += p->kv_blocks[b].tok_len;
@@ -124,6 +126,7 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   L->off_bwd_items = off;   off = align(off + sizeof(BwdItem) * (size_t)std::max<int64_t>(1, L->n_bwd_items));
   L->off_merge_items = off; off = align(off + sizeof(MergeItem) * (size_t)std::max<int64_t>(1, L->n_merge_items));
   L->off_slot_rh = off;     off = align(off + sizeof(int32_t) * (size_t)std::max(1, p->n_slots));
+  L->off_dq_items = off;    off = align(off + sizeof(FwdItem) * (size_t)std::max<int64_t>(1, L->n_dq_items));
   L->off_delta = off;       off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
   L->total = off;
   return FCP_OK;
@@ -307,11 +310,11 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     for (int s = 0; s < p->n_slots; s++) {
       const fcp_slot& sl = p->slots[s];
       const fcp_block& qb = p->q_blocks[sl.q_blk];
-      const int n_tiles = (int)ceil_div(qb.tok_len, kFwdTileM);
+      const int n_tiles = (int)ceil_div(qb.tok_len, L.fwd_tile_m);
       std::vector<int64_t> tile_w(n_tiles, 0);
       for (int t = n_tiles - 1; t >= 0; t--) {
-        const int off = t * kFwdTileM;
-        const int rows = std::min(kFwdTileM, qb.tok_len - off);
+        const int off = t * L.fwd_tile_m;
+        const int rows = std::min(L.fwd_tile_m, qb.tok_len - off);
         for (int i = sl.pair_begin; i < sl.pair_begin + sl.n_pairs; i++) {
           const int kvlen = dpairs[i].kv_len;
           const int cols = dpairs[i].kind == FCP_KIND_DIAG ? std::min(kvlen, off + rows) : kvlen;
@@ -322,8 +325,8 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
         std::vector<FwdItem> items;
         int64_t w = 0;
         for (int t = n_tiles - 1; t >= 0; t--) {       // later tiles of a DIAG pair are heavier
-          const int off = t * kFwdTileM;
-          const int rows = std::min(kFwdTileM, qb.tok_len - off);
+          const int off = t * L.fwd_tile_m;
+          const int rows = std::min(L.fwd_tile_m, qb.tok_len - off);
           for (int hh = 0; hh < G; hh++) {
             items.push_back({qb.tok_start + off, rows, sl.row_start + off, off, sl.pair_begin, sl.n_pairs,
                              g * G + hh, 0});
@@ -382,6 +385,50 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     spread_over_xcds(groups, weight, &flat, hdr->bwd_begin);
     if ((int64_t)flat.size() != L.n_bwd_items) { set_error("internal: backward item count mismatch"); return FCP_ERR_INVALID_ARG; }
     if (!flat.empty()) std::memcpy(host.data() + L.off_bwd_items, flat.data(), flat.size() * sizeof(BwdItem));
+  }
+  // ---- backward dQ: query-stationary items over ALL pairs of a query block (its slots are
+  // consecutive, so their pairs form one range); one group per (query block, KV head).
+  {
+    std::vector<int32_t> pb(p->n_q_blocks, 0), pn(p->n_q_blocks, 0);
+    for (int s = 0; s < p->n_slots; s++) {
+      const fcp_slot& sl = p->slots[s];
+      if (pn[sl.q_blk] == 0) pb[sl.q_blk] = sl.pair_begin;
+      pn[sl.q_blk] += sl.n_pairs;
+    }
+    std::vector<std::vector<FwdItem>> groups;
+    std::vector<int64_t> weight;
+    groups.reserve((size_t)p->n_q_blocks * p->n_kv_heads);
+    for (int b = 0; b < p->n_q_blocks; b++) {
+      const fcp_block& qb = p->q_blocks[b];
+      const int n_tiles = (int)ceil_div(qb.tok_len, kFwdTileM);
+      std::vector<int64_t> tile_w(n_tiles, 0);
+      for (int t = 0; t < n_tiles; t++) {
+        const int off = t * kFwdTileM;
+        const int rows = std::min(kFwdTileM, qb.tok_len - off);
+        for (int i = pb[b]; i < pb[b] + pn[b]; i++) {
+          const int cols = dpairs[i].kind == FCP_KIND_DIAG ? std::min(dpairs[i].kv_len, off + rows) : dpairs[i].kv_len;
+          tile_w[t] += (int64_t)rows * cols;
+        }
+      }
+      for (int g = 0; g < p->n_kv_heads; g++) {
+        std::vector<FwdItem> items;
+        int64_t w = 0;
+        for (int t = n_tiles - 1; t >= 0; t--) {
+          const int off = t * kFwdTileM;
+          const int rows = std::min(kFwdTileM, qb.tok_len - off);
+          for (int hh = 0; hh < G; hh++) {
+            items.push_back({qb.tok_start + off, rows, qb.tok_start + off, off, pb[b], pn[b], g * G + hh, 0});
+            w += tile_w[t];
+          }
+        }
+        groups.push_back(std::move(items));
+        weight.push_back(w);
+      }
+    }
+    std::vector<FwdItem> flat;
+    spread_over_xcds(groups, weight, &flat, hdr->dq_begin);
+    if ((int64_t)flat.size() != L.n_dq_items) { set_error("internal: dQ item count mismatch"); return FCP_ERR_INVALID_ARG; }
+    if (!flat.empty()) std::memcpy(host.data() + L.off_dq_items, flat.data(), flat.size() * sizeof(FwdItem));
   }
   // ---- merge: row-head chunks per query block; slots of a query block are consecutive.
   {

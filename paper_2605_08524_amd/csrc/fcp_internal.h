@@ -10,7 +10,7 @@
 namespace fcp {
 
 constexpr int kNumXcd = 8;          // MI355X: 8 XCDs, each with its own L2; workgroup b runs on XCD b % 8
-constexpr int kFwdTileM = 128;      // query rows per forward work item (4 waves x 32 rows)
+constexpr int kFwdTileM = 128;      // query rows per query-stationary work item (4 waves x 32 rows)
 constexpr int kBwdTileN = 128;      // KV rows per backward work item (4 waves x 32 rows)
 constexpr int kMergeChunk = 1024;   // (row, head) entries per merge work item
 
@@ -26,17 +26,22 @@ struct MergeItem { int32_t out_rh, n_rh, slot_begin, n_slots, rh_off, pad0, pad1
 struct WsHeader {
   int32_t fwd_counter[kNumXcd];
   int32_t bwd_counter[kNumXcd];
-  int32_t fwd_done, bwd_done, pad0[6];
+  int32_t dq_counter[kNumXcd];
+  int32_t fwd_done, bwd_done, dq_done, pad0[5];
   int32_t fwd_begin[kNumXcd + 1];   // item range of each XCD queue
   int32_t pad1[7];
   int32_t bwd_begin[kNumXcd + 1];
   int32_t pad2[7];
+  int32_t dq_begin[kNumXcd + 1];
+  int32_t pad3[7];
+  int32_t zeros[64];                // 256-byte zero page: source of LDS-DMA loads past a ragged end
 };
 
 // Byte offsets of the workspace sections, a pure function of the problem's counts.
 struct WsLayout {
-  int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, t_q, t_kv;
-  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_delta, total;
+  int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, n_dq_items, t_q, t_kv;
+  int fwd_tile_m;   // query rows per forward item, chosen per problem
+  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_delta, total;
 };
 
 int validate_problem(const fcp_problem* p);           // host; sets the error text

@@ -57,6 +57,44 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const unsigned char* lo, const uns
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
+// Byte offset of 16-byte chunk c of row r in an LDS tile.  Rows are unpadded (D*2 bytes) because
+// tiles are filled by LDS-DMA loads that write 1 KB of consecutive LDS per wave instruction; the
+// chunk index is XOR-swizzled with the row so that both access patterns are conflict free for
+// D = 128 (rows of exactly 64 banks): row-wise ds_read_b128 (16 lanes = 16 consecutive rows, one
+// chunk column) and transpose reads (32 lanes = 4 consecutive rows x 4 consecutive chunks).
+template <int D>
+__device__ __forceinline__ int swz(int r) {
+  if constexpr (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  else return (r >> 1) & 7;
+}
+template <int D>
+__device__ __forceinline__ int tile_off(int r, int c) { return r * (D * 2) + ((c ^ swz<D>(r)) << 4); }
+
+// Asynchronous copy of a [ROWS x D] bf16 tile from global memory straight into LDS (no
+// registers): each global_load_lds_dwordx4 moves 64 x 16 B into 1 KB of consecutive LDS, so lane
+// i of instruction n fills physical chunk i % (D/8) of row n*(1024/(2D)) + i/(D/8) and fetches
+// the logical chunk that the swizzle places there.  Rows >= valid_rows are filled from a zero
+// page.  Completion: s_waitcnt vmcnt(0) by the issuing wave, then a workgroup barrier.
+template <int D, int ROWS, int NWAVES>
+__device__ __forceinline__ void tile_dma(unsigned char* lds_tile, const uint16_t* src, int64_t row_stride,
+                                         int valid_rows, const unsigned char* zeros, int wave, int lane) {
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NI = ROWS / RPI;
+  static_assert(NI % NWAVES == 0, "tile does not split evenly over the waves");
+#pragma unroll
+  for (int n = 0; n < NI / NWAVES; n++) {
+    const int inst = n * NWAVES + wave;
+    const int r = inst * RPI + lane / CPR;
+    const int pc = lane % CPR;
+    const unsigned char* gp = zeros + pc * 16;
+    if (r < valid_rows) gp = reinterpret_cast<const unsigned char*>(src + (int64_t)r * row_stride + ((pc ^ swz<D>(r)) << 3));
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                     (__attribute__((address_space(3))) void*)(lds_tile + inst * 1024), 16, 0, 0);
+  }
+}
+__device__ __forceinline__ void dma_wait() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+template <int D> constexpr int tile_bytes(int rows) { return rows * D * 2; }
+
 // Pop one item index from the eight XCD queues, own queue first, then stealing.  Returns -1
 // when every queue is dry.  Every call terminates: each queue is probed at most once.
 __device__ __forceinline__ int pop_item(int32_t* counter, const int32_t* begin) {
@@ -82,23 +120,15 @@ __device__ __forceinline__ void retire(int32_t* counter, int32_t* done) {
 }
 
 // =====================================================================================
-// Forward: partial attention of one (slot, query tile, query head) item.
+// Forward: partial attention of one (slot, 128-row query tile, query head) item.
 // The wave computes S^T = K Q^T so that a lane owns one query row (column of S^T): row
 // statistics need one cross-half exchange, and the exponentiated accumulator is, as is,
-// the B operand of O^T += V^T P^T.
+// the B operand of O^T += V^T P^T.  K/V tiles of 64 rows are double-buffered in LDS and
+// filled by LDS-DMA one tile ahead; two workgroups per CU (two waves per SIMD) let one wave's
+// softmax overlap the other's MFMAs.
 // =====================================================================================
 constexpr int kFwdTileN = 64;   // KV rows per LDS tile
-
-template <int D>
-struct FwdCfg {
-  static constexpr int kKStride = D * 2 + 16;   // bytes; +16 keeps 16 rows x 16 B on distinct banks
-  static constexpr int kVStride = D * 2 + 64;   // bytes; +64 keeps 4 rows x 64 B on distinct banks
-  static constexpr int kKBytes = kFwdTileN * kKStride;
-  static constexpr int kVBytes = kFwdTileN * kVStride;
-  static constexpr int kChunksPerRow = D / 8;                       // 16-byte chunks
-  static constexpr int kChunksPerThread = kFwdTileN * kChunksPerRow / 256;
-  static constexpr int kRowsPerPass = 256 / kChunksPerRow;
-};
+constexpr float kRescaleSlack = 8.0f;   // log2 units
 
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
@@ -108,13 +138,40 @@ struct FwdArgs {
   float scale_log2;   // softmax scale * log2(e)
 };
 
+// Iterator over the KV tiles of an item's pairs, in pair order.  For a DIAG pair only the
+// columns up to the tile's last query row are visited.
+struct TileIter {
+  const DevPair* pairs;
+  int pair, pair_end, c0, ncols, row_hi;   // row_hi = tile_off + q_rows (first row past the tile)
+  DevPair cur;
+  bool more;
+  __device__ __forceinline__ void load_pair() {
+    cur = pairs[pair];
+    ncols = cur.kind == FCP_KIND_DIAG ? min(cur.kv_len, row_hi) : cur.kv_len;
+  }
+  __device__ __forceinline__ void init(const DevPair* p, int begin, int n, int row_hi_) {
+    pairs = p; pair = begin; pair_end = begin + n; c0 = 0; ncols = 0; row_hi = row_hi_;
+    cur = DevPair{0, 0, 0, 0};
+    more = n > 0;
+    if (more) load_pair();
+  }
+  __device__ __forceinline__ void advance() {
+    c0 += kFwdTileN;
+    if (c0 >= ncols) {
+      pair++;
+      c0 = 0;
+      if (pair < pair_end) load_pair(); else more = false;
+    }
+  }
+};
+
 template <int D>
-__global__ void __launch_bounds__(256) fwd_kernel(FwdArgs a) {
-  using C = FwdCfg<D>;
+__global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
   constexpr int KC = D / 16;      // k-chunks of the QK^T contraction
   constexpr int DT = D / 32;      // row tiles of O^T
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k[C::kKBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_v[C::kVBytes];
+  constexpr int TB = tile_bytes<D>(kFwdTileN);
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_k[2][TB];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_v[2][TB];
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -122,9 +179,17 @@ __global__ void __launch_bounds__(256) fwd_kernel(FwdArgs a) {
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;     // elements
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
-  const int ld_chunk = tid % C::kChunksPerRow, ld_row = tid / C::kChunksPerRow;
-  // transpose-read address pattern inside a 16-lane group
+  const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  // transpose-read pattern inside a 16-lane group: row tr_row, 4 columns from tr_col
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  int tr_lo[DT], tr_hi[DT], kk_off[KC];   // swizzled offsets; the swizzle has period 16 in the row
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++) {
+    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+  }
+#pragma unroll
+  for (int kc = 0; kc < KC; kc++) kk_off[kc] = tile_off<D>(l32, 2 * kc + g);
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->fwd_counter, a.hdr->fwd_begin);
@@ -136,6 +201,8 @@ __global__ void __launch_bounds__(256) fwd_kernel(FwdArgs a) {
     const int my_row = wave * 32 + l32;                      // row inside the tile
     const bool row_ok = my_row < it.q_rows;
     const int wave_row_lo = it.tile_off + wave * 32;         // rows of this wave inside the block
+    const uint16_t* kbase = a.k + (int64_t)kvh * D;
+    const uint16_t* vbase = a.v + (int64_t)kvh * D;
 
     // Q^T fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d per k-chunk.
     bf16x8 qf[KC];
@@ -155,128 +222,111 @@ __global__ void __launch_bounds__(256) fwd_kernel(FwdArgs a) {
       for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // Tile iterator over (pair, column offset).
-    int pair = it.pair_begin;
-    const int pair_end = it.pair_begin + it.n_pairs;
-    bool more = it.n_pairs > 0;       // an empty slot yields O = 0, LSE = -inf
-    DevPair cur = {0, 0, 0, 0};
-    if (more) cur = a.pairs[pair];
-    int c0 = 0;
-    auto ncols_of = [&](const DevPair& p) {
-      return p.kind == FCP_KIND_DIAG ? min(p.kv_len, it.tile_off + it.q_rows) : p.kv_len;
+    TileIter ti;                      // names the next tile to LOAD
+    ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
+    auto dma = [&](int buf) {
+      const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
+      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
+      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
     };
-    int ncols = ncols_of(cur);
+    DevPair tp = ti.cur;              // the tile being computed
+    int tc0 = 0;
+    bool have = ti.more;              // an empty slot yields O = 0, LSE = -inf
+    if (have) { dma(0); ti.advance(); }
+    dma_wait();
+    __syncthreads();
+    int buf = 0;
+    while (have) {
+      // next tile into the other buffer (its readers finished before the last barrier)
+      const DevPair np = ti.cur;
+      const int nc0 = ti.c0;
+      const bool nhave = ti.more;
+      if (nhave) { dma(buf ^ 1); ti.advance(); }
 
-    u32x4 pk[C::kChunksPerThread], pv[C::kChunksPerThread];
-    auto issue_loads = [&](const DevPair& p, int col0) {
-#pragma unroll
-      for (int i = 0; i < C::kChunksPerThread; i++) {
-        const int r = col0 + ld_row + i * C::kRowsPerPass;
-        u32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-        if (r < p.kv_len) {
-          const int64_t off = (int64_t)(p.kv_start + r) * kv_row_stride + (int64_t)kvh * D + ld_chunk * 8;
-          zk = *reinterpret_cast<const u32x4*>(a.k + off);
-          zv = *reinterpret_cast<const u32x4*>(a.v + off);
-        }
-        pk[i] = zk; pv[i] = zv;
-      }
-    };
-    if (more) issue_loads(cur, 0);
-
-    while (more) {
-      const DevPair tp = cur;     // the tile about to be computed
-      const int tc0 = c0;
-      __syncthreads();            // everyone is done reading the previous tile
-#pragma unroll
-      for (int i = 0; i < C::kChunksPerThread; i++) {
-        const int r = ld_row + i * C::kRowsPerPass;
-        *reinterpret_cast<u32x4*>(lds_k + r * C::kKStride + ld_chunk * 16) = pk[i];
-        *reinterpret_cast<u32x4*>(lds_v + r * C::kVStride + ld_chunk * 16) = pv[i];
-      }
-      __syncthreads();
-      // advance the iterator and prefetch the next tile into registers
-      c0 += kFwdTileN;
-      if (c0 >= ncols) {
-        pair++;
-        c0 = 0;
-        if (pair < pair_end) { cur = a.pairs[pair]; ncols = ncols_of(cur); } else { more = false; }
-      }
-      if (more) issue_loads(cur, c0);
-
+      const unsigned char* tk = lds_k[buf];
+      const unsigned char* tv = lds_v[buf];
       const bool diag = tp.kind == FCP_KIND_DIAG;
       // a wave whose rows all lie above this tile's first column has nothing visible in it
-      if (diag && tc0 > wave_row_lo + 31) continue;
-
-      // ---- S^T = K Q^T  (two 32-row tiles of KV)
-      f32x16 s[2];
+      if (!(diag && tc0 > wave_row_lo + 31)) {
+        // ---- S^T = K Q^T  (two 32-row tiles of KV)
+        f32x16 s[2];
 #pragma unroll
-      for (int rt = 0; rt < 2; rt++)
+        for (int rt = 0; rt < 2; rt++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) s[rt][r] = 0.f;
+          for (int r = 0; r < 16; r++) s[rt][r] = 0.f;
 #pragma unroll
-      for (int kc = 0; kc < KC; kc++) {
+        for (int kc = 0; kc < KC; kc++) {
 #pragma unroll
-        for (int rt = 0; rt < 2; rt++) {
-          const u32x4 kk = *reinterpret_cast<const u32x4*>(lds_k + (rt * 32 + l32) * C::kKStride + kc * 32 + g * 16);
-          s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s[rt], 0, 0, 0);
+          for (int rt = 0; rt < 2; rt++) {
+            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[kc]);
+            s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s[rt], 0, 0, 0);
+          }
         }
-      }
-      // ---- mask (only tiles that touch the diagonal or the ragged end)
-      const bool need_mask = (tc0 + kFwdTileN > tp.kv_len) || (diag && tc0 + kFwdTileN - 1 > wave_row_lo);
-      if (need_mask) {
-        const int limit = diag ? min(tp.kv_len - 1, it.tile_off + my_row) : tp.kv_len - 1;   // last visible column
+        // ---- mask (only tiles that touch the diagonal or the ragged end)
+        const bool need_mask = (tc0 + kFwdTileN > tp.kv_len) || (diag && tc0 + kFwdTileN - 1 > wave_row_lo);
+        if (need_mask) {
+          const int limit = diag ? min(tp.kv_len - 1, it.tile_off + my_row) : tp.kv_len - 1;   // last visible column
+#pragma unroll
+          for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+              const int col = tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+              if (col > limit) s[rt][r] = -INFINITY;
+            }
+        }
+        // ---- online softmax in the log2 domain.  The reference maximum m_run only moves when some
+        // row's maximum exceeds it by more than kRescaleSlack (a wave-uniform decision): any reference
+        // gives the same O and LSE as long as exp2 stays in range, and P <= 2^slack is harmless in
+        // bf16/fp32.  Most tiles therefore skip the rescaling of the O accumulators.
+        float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx = fmaxf(fmaxf(mx, s[0][r]), s[1][r]);
+        mx = fmaxf(mx, xor32(mx)) * a.scale_log2;
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+          const float m_new = fmaxf(m_run, mx);
+          const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // m_run = -inf -> 0
+          m_run = m_new;
+          l_run *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+        }
+        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+        float rs = 0.f;
 #pragma unroll
         for (int rt = 0; rt < 2; rt++)
 #pragma unroll
           for (int r = 0; r < 16; r++) {
-            const int col = tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (col > limit) s[rt][r] = -INFINITY;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rt][r], a.scale_log2, -m_use));
+            s[rt][r] = p;
+            rs += p;
           }
-      }
-      // ---- online softmax in the log2 domain
-      float mx = s[0][0];
+        l_run += rs;
+        // ---- O^T += V^T P^T ; P^T's accumulator registers are its B operand
 #pragma unroll
-      for (int rt = 0; rt < 2; rt++)
+        for (int rt = 0; rt < 2; rt++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[rt][r]);
-      mx = fmaxf(mx, xor32(mx));
-      const float m_new = fmaxf(m_run, mx * a.scale_log2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      m_run = m_new;
-      float rs = 0.f;
+          for (int j = 0; j < 2; j++) {
+            u32x4 pb;
+            pb[0] = pack_bf16(s[rt][8 * j + 0], s[rt][8 * j + 1]);
+            pb[1] = pack_bf16(s[rt][8 * j + 2], s[rt][8 * j + 3]);
+            pb[2] = pack_bf16(s[rt][8 * j + 4], s[rt][8 * j + 5]);
+            pb[3] = pack_bf16(s[rt][8 * j + 6], s[rt][8 * j + 7]);
+            const unsigned char* base = tv + (rt * 32 + 16 * j) * (D * 2);
 #pragma unroll
-      for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rt][r], a.scale_log2, -m_use));
-          s[rt][r] = p;
-          rs += p;
-        }
-      l_run = l_run * alpha + rs;
-#pragma unroll
-      for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
-      // ---- O^T += V^T P^T ; P^T's accumulator registers are its B operand
-#pragma unroll
-      for (int rt = 0; rt < 2; rt++) {
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-          u32x4 pb;
-          pb[0] = pack_bf16(s[rt][8 * j + 0], s[rt][8 * j + 1]);
-          pb[1] = pack_bf16(s[rt][8 * j + 2], s[rt][8 * j + 3]);
-          pb[2] = pack_bf16(s[rt][8 * j + 4], s[rt][8 * j + 5]);
-          pb[3] = pack_bf16(s[rt][8 * j + 6], s[rt][8 * j + 7]);
-          const int kv0 = rt * 32 + 16 * j + 4 * g;
-          const unsigned char* base = lds_v + (kv0 + tr_row) * C::kVStride + tr_col * 2;
-#pragma unroll
-          for (int dt = 0; dt < DT; dt++) {
-            const bf16x8 vt = lds_tr_pair(base + dt * 64, base + 8 * C::kVStride + dt * 64);
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, as_bf16x8(pb), o[dt], 0, 0, 0);
+            for (int dt = 0; dt < DT; dt++) {
+              const bf16x8 vt = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
+              o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, as_bf16x8(pb), o[dt], 0, 0, 0);
+            }
           }
         }
       }
+      tp = np; tc0 = nc0; have = nhave;
+      dma_wait();
+      __syncthreads();
+      buf ^= 1;
     }
 
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
@@ -379,62 +429,90 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32,
   if (e < n_rh && ln == 0) delta[e] = acc;
 }
 
-__global__ void __launch_bounds__(256) zero_kernel(f32x4* p, int64_t n4) {
-  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) p[i] = z;
-}
-
 // =====================================================================================
-// Backward: one (KV tile of 128 rows, KV head) item; each wave keeps 32 KV rows' dK^T and
-// dV^T accumulators in registers across every dependent query block and the G query heads
-// of the group; dQ is reduced over the tile's 128 KV rows through LDS and added atomically.
-// Per 32-row query step:
-//   S = Q K^T, dP = dO V^T          (A from LDS tiles, B = the wave's K / V fragments)
-//   P = exp2(S*c - LSE*log2e), dS = P o (dP - D) * scale
-//   dV^T += dO^T P, dK^T += Q^T dS  (A by transpose reads, B = accumulator registers)
-//   dQ[:, 32-wide slice of d] = dS K (dS^T staged in LDS, K by transpose-read fragments)
+// Backward, part 1 -- dK and dV.  Item = (KV tile of 128 rows, KV head); workgroup of 8 waves.
+// Wave w works on KV rows 32*(w%4) .. +32 of the tile in one of two roles, so that the two
+// waves sharing a SIMD split the four contractions evenly and neither holds more than one
+// accumulator set (no register spills at two waves per SIMD):
+//   role 0 (w < 4):  S = Q K^T -> P = exp2(S*c - LSE*log2e) -> hands P (fp32) to its partner
+//                    through LDS;  dV^T += dO^T P
+//   role 1 (w >= 4): dP = dO V^T;  dS = P o (dP - D) * scale;  dK^T += Q^T dS
+// S and dP take A from the Q / dO tiles in LDS (row-wise reads) and B from the wave's K or V
+// fragments in registers; dV^T and dK^T take A by transpose reads of the same tiles and B from
+// the accumulator registers.  Accumulators live in registers across every dependent query block
+// and the G query heads of the group; each dK / dV row has exactly one writer (plain stores).
+// Q / dO tiles of 32 rows are triple-buffered and filled by LDS-DMA two steps ahead: one
+// workgroup barrier per step (the one that publishes P).
+// dQ is not produced here: accumulating it across KV tiles needs fp32 atomics, and the chip
+// sustains only about 1.35 TB/s of them (measured), several times below what this kernel would
+// emit.  dq_kernel below recomputes S and dP query-stationary instead.
 // =====================================================================================
-template <int D>
-struct BwdCfg {
-  static constexpr int kTStride = D * 2 + 16;            // Q / dO / K tile row stride in bytes
-  static constexpr int kKBytes = kBwdTileN * kTStride;
-  static constexpr int kQBytes = 32 * kTStride;
-  static constexpr int kDsBytes = kBwdTileN * 64;        // dS^T [128 kv][32 q] bf16, swizzled
-  static constexpr int kChunksPerRow = D / 8;
-  static constexpr int kQChunksPerThread = 32 * kChunksPerRow / 256;   // 2 (D=128) or 1 (D=64)
-  static constexpr int kRowsPerPass = 256 / kChunksPerRow;
-};
-
 struct BwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse; const float* delta;
   float* dq; float* dk; float* dv;
-  WsHeader* hdr; const BwdDep* deps; const BwdItem* items;
+  WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const FwdItem* dq_items;
   int32_t n_q_heads, n_kv_heads;
   float scale, scale_log2;
 };
 
+// Iterator over the 32-row query steps of a backward item: rows, then the G query heads of
+// the group, then the dependent query blocks.  A DIAG dependency starts at the tile's own rows.
+struct StepIter {
+  const BwdDep* deps;
+  int dep, n_deps, hh, group, q0, first_diag;
+  BwdDep cur;
+  bool more;
+  __device__ __forceinline__ int first_q0() const { return cur.kind == FCP_KIND_DIAG ? first_diag : 0; }
+  __device__ __forceinline__ void init(const BwdDep* d, int n, int group_, int tile_off) {
+    deps = d; dep = 0; n_deps = n; hh = 0; group = group_; first_diag = tile_off & ~31; q0 = 0;
+    cur = BwdDep{0, 0, 0, 0};
+    more = n > 0;
+    if (more) { cur = deps[0]; q0 = first_q0(); }
+  }
+  __device__ __forceinline__ void advance() {
+    q0 += 32;
+    if (q0 >= cur.q_len) {
+      hh++;
+      if (hh < group) {
+        q0 = first_q0();
+      } else {
+        hh = 0;
+        dep++;
+        if (dep < n_deps) { cur = deps[dep]; q0 = first_q0(); } else { more = false; }
+      }
+    }
+  }
+};
+
 template <int D>
-__global__ void __launch_bounds__(256) bwd_kernel(BwdArgs a) {
-  using C = BwdCfg<D>;
+__global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char lds_kt[C::kKBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_q[C::kQBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_do[C::kQBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_ds[C::kDsBytes];
-  __shared__ __attribute__((aligned(16))) float lds_lse[32];
-  __shared__ __attribute__((aligned(16))) float lds_dl[32];
+  constexpr int TB = tile_bytes<D>(32);
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_q[3][TB];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_do[3][TB];
+  __shared__ __attribute__((aligned(16))) unsigned char lds_p[2][4][4096];   // [buffer][kv sub-tile][q4][lane] float4
+  __shared__ __attribute__((aligned(16))) float lds_lse[3][32];
+  __shared__ __attribute__((aligned(16))) float lds_dl[3][32];
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = wave & 3, role = wave >> 2;
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
-  const int ld_chunk = tid % C::kChunksPerRow, ld_row = tid / C::kChunksPerRow;
+  const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const bool dq_wave = wave < DT;     // waves that own a 32-wide slice of d for dQ
+  int tr_lo[DT], tr_hi[DT], row_off[KC];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++) {
+    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+  }
+#pragma unroll
+  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g);
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->bwd_counter, a.hdr->bwd_begin);
@@ -442,76 +520,41 @@ __global__ void __launch_bounds__(256) bwd_kernel(BwdArgs a) {
     const int item_idx = s_item;
     if (item_idx < 0) break;
     const BwdItem it = a.items[item_idx];
-    const int my_kv = wave * 32 + l32;                 // KV row inside the tile
+    const int my_kv = sub * 32 + l32;                  // KV row inside the tile
     const bool kv_ok = my_kv < it.kv_rows;
 
-    // K tile -> LDS (zero-filled past the ragged end), for the transpose-read fragments of dQ.
-    for (int r = ld_row; r < kBwdTileN; r += C::kRowsPerPass) {
-      u32x4 z = {0, 0, 0, 0};
-      if (r < it.kv_rows)
-        z = *reinterpret_cast<const u32x4*>(a.k + (int64_t)(it.kv_start + r) * kv_row_stride + (int64_t)it.kv_head * D + ld_chunk * 8);
-      *reinterpret_cast<u32x4*>(lds_kt + r * C::kTStride + ld_chunk * 16) = z;
-    }
-    // B operands of S = Q K^T and dP = dO V^T: lane = KV row, 8 consecutive d per k-chunk.
-    bf16x8 kf[KC], vf[KC];
+    // B operand of this wave's first contraction: K rows (role 0) or V rows (role 1);
+    // lane = KV row, 8 consecutive d per k-chunk.
+    bf16x8 bfr[KC];
     {
+      const uint16_t* src = role ? a.v : a.k;
       const int64_t off = (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D + 8 * g;
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) {
-        u32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-        if (kv_ok) {
-          zk = *reinterpret_cast<const u32x4*>(a.k + off + kc * 16);
-          zv = *reinterpret_cast<const u32x4*>(a.v + off + kc * 16);
-        }
-        kf[kc] = as_bf16x8(zk); vf[kc] = as_bf16x8(zv);
+        u32x4 z = {0, 0, 0, 0};
+        if (kv_ok) z = *reinterpret_cast<const u32x4*>(src + off + kc * 16);
+        bfr[kc] = as_bf16x8(z);
       }
     }
-    __syncthreads();
-    // B operands of dQ = dS K for this wave's d slice: lane = d column, k-slot (g, i) = kv 16j + 8g + i.
-    bf16x8 kb[kBwdTileN / 16];
-    if (dq_wave) {
-#pragma unroll
-      for (int j = 0; j < kBwdTileN / 16; j++) {
-        const unsigned char* base = lds_kt + (16 * j + 8 * g + tr_row) * C::kTStride + (wave * 32 + tr_col) * 2;
-        kb[j] = lds_tr_pair(base, base + 4 * C::kTStride);
-      }
-    }
-    f32x16 dkt[DT], dvt[DT];
+    f32x16 acc[DT];     // dV^T (role 0) or dK^T (role 1): rows = d, cols = this wave's KV rows
 #pragma unroll
     for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) { dkt[dt][r] = 0.f; dvt[dt][r] = 0.f; }
+      for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
 
-    // Step iterator over (dependency, query head of the group, 32-row query step).
-    const int n_deps = it.n_deps;
-    int dep = 0, hh = 0, q0 = 0;
-    BwdDep cd = {0, 0, 0, 0};
-    auto first_q0 = [&](const BwdDep& d) { return d.kind == FCP_KIND_DIAG ? (it.tile_off & ~31) : 0; };
-    bool more = n_deps > 0;
-    if (more) {
-      cd = a.deps[it.dep_begin];
-      q0 = first_q0(cd);
-      // a DIAG dependency always has rows at or below this tile's first row (same block)
-    }
-    u32x4 pq[C::kQChunksPerThread], pdo[C::kQChunksPerThread];
+    StepIter si;        // names the next step to LOAD
+    si.init(a.deps + it.dep_begin, it.n_deps, group, it.tile_off);
     float p_lse = 0.f, p_dl = 0.f;
-    auto issue_loads = [&](const BwdDep& d, int head, int row0) {
-#pragma unroll
-      for (int i = 0; i < C::kQChunksPerThread; i++) {
-        const int r = row0 + ld_row + i * C::kRowsPerPass;
-        u32x4 zq = {0, 0, 0, 0}, zd = {0, 0, 0, 0};
-        if (r < d.q_len) {
-          const int64_t off = (int64_t)(d.q_start + r) * q_row_stride + (int64_t)head * D + ld_chunk * 8;
-          zq = *reinterpret_cast<const u32x4*>(a.q + off);
-          zd = *reinterpret_cast<const u32x4*>(a.d_o + off);
-        }
-        pq[i] = zq; pdo[i] = zd;
-      }
+    // Waves 0-3 fetch the Q tile, waves 4-7 the dO tile; the first 32 threads fetch LSE and D.
+    auto dma = [&](int buf) {
+      const int head = it.kv_head * group + si.hh;
+      const uint16_t* src = (role ? a.d_o : a.q) + (int64_t)(si.cur.q_start + si.q0) * q_row_stride + (int64_t)head * D;
+      tile_dma<D, 32, 4>(role ? lds_do[buf] : lds_q[buf], src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane);
       if (tid < 32) {
-        const int r = row0 + tid;
+        const int r = si.q0 + tid;
         float l = INFINITY, dl = 0.f;      // rows past the end get P = exp2(-inf) = 0
-        if (r < d.q_len) {
-          const int64_t rh = (int64_t)(d.q_start + r) * a.n_q_heads + head;
+        if (r < si.cur.q_len) {
+          const int64_t rh = (int64_t)(si.cur.q_start + r) * a.n_q_heads + head;
           l = a.lse[rh];
           if (l == -INFINITY) l = INFINITY;  // a row that saw no key has no gradient
           dl = a.delta[rh];
@@ -519,136 +562,272 @@ __global__ void __launch_bounds__(256) bwd_kernel(BwdArgs a) {
         p_lse = l * kLog2e; p_dl = dl * a.scale;
       }
     };
-    if (more) issue_loads(cd, it.kv_head * group + hh, q0);
+    auto publish_scalars = [&](int buf) { if (tid < 32) { lds_lse[buf][tid] = p_lse; lds_dl[buf][tid] = p_dl; } };
 
-    while (more) {
-      const BwdDep td = cd;
-      const int t_head = it.kv_head * group + hh;
-      const int tq0 = q0;
-      __syncthreads();     // previous step's readers of the Q/dO/dS tiles are done
-#pragma unroll
-      for (int i = 0; i < C::kQChunksPerThread; i++) {
-        const int r = ld_row + i * C::kRowsPerPass;
-        *reinterpret_cast<u32x4*>(lds_q + r * C::kTStride + ld_chunk * 16) = pq[i];
-        *reinterpret_cast<u32x4*>(lds_do + r * C::kTStride + ld_chunk * 16) = pdo[i];
-      }
-      if (tid < 32) { lds_lse[tid] = p_lse; lds_dl[tid] = p_dl; }
-      __syncthreads();
-      // advance: rows, then heads of the group, then dependencies
-      q0 += 32;
-      if (q0 >= cd.q_len) {
-        hh++;
-        if (hh < group) {
-          q0 = first_q0(cd);
-        } else {
-          hh = 0;
-          dep++;
-          if (dep < n_deps) { cd = a.deps[it.dep_begin + dep]; q0 = first_q0(cd); } else { more = false; }
-        }
-      }
-      if (more) issue_loads(cd, it.kv_head * group + hh, q0);
-
-      // ---- S = Q K^T and dP = dO V^T   (rows = query, cols = this wave's 32 KV rows)
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int kc = 0; kc < KC; kc++) {
-        const u32x4 qa = *reinterpret_cast<const u32x4*>(lds_q + l32 * C::kTStride + kc * 32 + g * 16);
-        const u32x4 da = *reinterpret_cast<const u32x4*>(lds_do + l32 * C::kTStride + kc * 32 + g * 16);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qa), kf[kc], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(da), vf[kc], dp, 0, 0, 0);
-      }
-      // ---- P and dS (register r = query row 8*(r/4) + 4g + r%4, lane = KV row)
+    // prologue: steps 0 and 1 in LDS before the first barrier
+    BwdDep td = si.cur;
+    int tq0 = si.q0;
+    bool have = si.more;
+    BwdDep nd = td;
+    int nq0 = 0;
+    bool nhave = false;
+    if (have) {
+      dma(0); dma_wait(); publish_scalars(0);
+      si.advance();
+      nd = si.cur; nq0 = si.q0; nhave = si.more;
+      if (nhave) { dma(1); dma_wait(); publish_scalars(1); si.advance(); }
+    }
+    __syncthreads();
+    int t = 0;          // step counter modulo 3 (tile buffers) and parity (P buffers)
+    int pbuf = 0;
+    while (have) {
+      const unsigned char* tq = lds_q[t];
+      const unsigned char* tdo = lds_do[t];
       const bool diag = td.kind == FCP_KIND_DIAG;
       const int kv_in_blk = it.tile_off + my_kv;
+      unsigned char* pslot = lds_p[pbuf][sub] + lane * 16;
+      f32x16 s;         // role 0: S then P;  role 1: dP then dS
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lds_lse[8 * q4 + 4 * g]);
-        const f32x4 dl4 = *reinterpret_cast<const f32x4*>(&lds_dl[8 * q4 + 4 * g]);
+      for (int r = 0; r < 16; r++) s[r] = 0.f;
+      // ---- phase 1: S = Q K^T (role 0) or dP = dO V^T (role 1); rows = query, cols = KV
+      {
+        const unsigned char* ta = role ? tdo : tq;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const int r = 4 * q4 + i;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], a.scale_log2, -lse4[i]));
-          if (diag && kv_in_blk > tq0 + 8 * q4 + 4 * g + i) p = 0.f;
-          s[r] = p;
-          dp[r] = p * __builtin_fmaf(dp[r], a.scale, -dl4[i]);
+        for (int kc = 0; kc < KC; kc++) {
+          const u32x4 aa = *reinterpret_cast<const u32x4*>(ta + row_off[kc]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aa), bfr[kc], s, 0, 0, 0);
         }
       }
-      u32x4 pb[2], dsb[2];
-#pragma unroll
-      for (int j = 0; j < 2; j++)
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          pb[j][i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
-          dsb[j][i] = pack_bf16(dp[8 * j + 2 * i], dp[8 * j + 2 * i + 1]);
-        }
-      // ---- stage dS^T for the dQ contraction: row = KV, 8-byte granules of 4 query rows, swizzled
-      {
-        unsigned char* row = lds_ds + my_kv * 64;
-        const int sw = (my_kv >> 2) & 7;
+      if (role == 0) {
+        // P (register r = query row 8*(r/4) + 4g + r%4, lane = KV row), handed to the partner wave
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
-          u32x2 w = {dsb[q4 >> 1][2 * (q4 & 1)], dsb[q4 >> 1][2 * (q4 & 1) + 1]};
-          *reinterpret_cast<u32x2*>(row + (((2 * q4 + g) ^ sw) * 8)) = w;
+          const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lds_lse[t][8 * q4 + 4 * g]);
+          f32x4 p4;
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * q4 + i], a.scale_log2, -lse4[i]));
+            if (diag && kv_in_blk > tq0 + 8 * q4 + 4 * g + i) p = 0.f;
+            s[4 * q4 + i] = p;
+            p4[i] = p;
+          }
+          *reinterpret_cast<f32x4*>(pslot + q4 * 1024) = p4;
         }
       }
-      // ---- dV^T += dO^T P ; dK^T += Q^T dS   (k-slot (g, i) of chunk j = query 16j + 8(i/4) + 4g + i%4)
+      dma_wait();                 // this wave's share of step t+1's tiles has landed
+      publish_scalars(t == 2 ? 0 : t + 1);
+      __syncthreads();            // P(t) visible; step t+1 complete; everyone is past step t-1
+      // ---- step t+2 into the buffer that step t-1 used
+      const BwdDep n2d = si.cur;
+      const int n2q0 = si.q0;
+      const bool n2have = si.more;
+      if (n2have) { dma(t == 0 ? 2 : t - 1); si.advance(); }
+      // ---- phase 2
+      if (role == 1) {
 #pragma unroll
-      for (int j = 0; j < 2; j++) {
-        const int qr = 16 * j + 4 * g + tr_row;
-        const unsigned char* bq = lds_q + qr * C::kTStride + tr_col * 2;
-        const unsigned char* bd = lds_do + qr * C::kTStride + tr_col * 2;
+        for (int q4 = 0; q4 < 4; q4++) {
+          const f32x4 p4 = *reinterpret_cast<const f32x4*>(pslot + q4 * 1024);
+          const f32x4 dl4 = *reinterpret_cast<const f32x4*>(&lds_dl[t][8 * q4 + 4 * g]);
 #pragma unroll
-        for (int dt = 0; dt < DT; dt++) {
-          const bf16x8 dot = lds_tr_pair(bd + dt * 64, bd + 8 * C::kTStride + dt * 64);
-          dvt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, as_bf16x8(pb[j]), dvt[dt], 0, 0, 0);
-          const bf16x8 qt = lds_tr_pair(bq + dt * 64, bq + 8 * C::kTStride + dt * 64);
-          dkt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, as_bf16x8(dsb[j]), dkt[dt], 0, 0, 0);
+          for (int i = 0; i < 4; i++) s[4 * q4 + i] = p4[i] * __builtin_fmaf(s[4 * q4 + i], a.scale, -dl4[i]);
         }
       }
-      __syncthreads();     // dS^T of all four waves is in LDS
-      // ---- dQ[32 q][this wave's 32 d] = dS[32 q][128 kv] K[128 kv][32 d]
-      if (dq_wave) {
-        f32x16 dq;
+      // dV^T += dO^T P (role 0) or dK^T += Q^T dS (role 1):
+      // k-slot (g, i) of chunk j = query 16j + 8(i/4) + 4g + i%4
+      {
+        const unsigned char* tt = role ? tq : tdo;
 #pragma unroll
-        for (int r = 0; r < 16; r++) dq[r] = 0.f;
+        for (int j = 0; j < 2; j++) {
+          u32x4 b;
 #pragma unroll
-        for (int j = 0; j < kBwdTileN / 16; j++) {
-          // A: lane = query row; k-slot (g, i) = kv 16j + 8g + i  -> two transpose reads of 4 KV rows
-          const int kv0 = 16 * j + 8 * g + tr_row;              // row this lane addresses (first read)
-          const int gran = (tr_col >> 2);                       // logical granule of 4 query rows
-          const unsigned char* lo = lds_ds + kv0 * 64 + ((gran ^ ((kv0 >> 2) & 7)) * 8);
-          const unsigned char* hi = lds_ds + (kv0 + 4) * 64 + ((gran ^ (((kv0 + 4) >> 2) & 7)) * 8);
-          dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_pair(lo, hi), kb[j], dq, 0, 0, 0);
-        }
-        float* dst = a.dq + (int64_t)td.q_start * q_row_stride + (int64_t)t_head * D + wave * 32 + l32;
+          for (int i = 0; i < 4; i++) b[i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
+          const unsigned char* base = tt + 16 * j * (D * 2);
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int qr = tq0 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (qr < td.q_len) unsafeAtomicAdd(dst + (int64_t)qr * q_row_stride, dq[r]);
+          for (int dt = 0; dt < DT; dt++) {
+            const bf16x8 at = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at, as_bf16x8(b), acc[dt], 0, 0, 0);
+          }
         }
       }
+      td = nd; tq0 = nq0; have = nhave;
+      nd = n2d; nq0 = n2q0; nhave = n2have;
+      t = (t == 2) ? 0 : t + 1;
+      pbuf ^= 1;
     }
 
-    // ---- epilogue: this item is the only writer of its dK / dV rows (plain stores)
+    // ---- epilogue: role 0 stores dV, role 1 stores dK (the only writer of these rows)
     if (kv_ok) {
-      float* kp = a.dk + (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
-      float* vp = a.dv + (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
+      float* dst = (role ? a.dk : a.dv) + (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
-          const int d0 = dt * 32 + 8 * q4 + 4 * g;
-          f32x4 wk = {dkt[dt][4 * q4], dkt[dt][4 * q4 + 1], dkt[dt][4 * q4 + 2], dkt[dt][4 * q4 + 3]};
-          f32x4 wv = {dvt[dt][4 * q4], dvt[dt][4 * q4 + 1], dvt[dt][4 * q4 + 2], dvt[dt][4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(kp + d0) = wk;
-          *reinterpret_cast<f32x4*>(vp + d0) = wv;
+          f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
+          *reinterpret_cast<f32x4*>(dst + dt * 32 + 8 * q4 + 4 * g) = w;
         }
     }
     __syncthreads();
   }
   if (tid == 0) retire(a.hdr->bwd_counter, &a.hdr->bwd_done);
+}
+
+// =====================================================================================
+// Backward, part 2 -- dQ.  Query-stationary like the forward: item = (query block, 128-row
+// tile, query head) over all pairs of the block; lane = query row.
+//   S^T = K Q^T, dP^T = V dO^T       (A = K / V rows from LDS, B = Q / dO fragments in registers)
+//   P^T = exp2(S^T*c - LSE*log2e), dS^T = P^T o (dP^T - D) * scale     (LSE, D per lane)
+//   dQ^T += K^T dS^T                 (A = K by transpose reads, B = accumulator registers)
+// K rows past a ragged end are zero in LDS, so their dS contributes nothing: only the
+// diagonal needs a mask.  Every dQ row has one writer: plain stores, deterministic.
+// =====================================================================================
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
+  constexpr int KC = D / 16;
+  constexpr int DT = D / 32;
+  constexpr int TB = tile_bytes<D>(kFwdTileN);
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_k[2][TB];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_v[2][TB];
+  __shared__ int s_item;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
+  const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
+  const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  int tr_lo[DT], tr_hi[DT], row_off[KC];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++) {
+    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+  }
+#pragma unroll
+  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g);
+
+  for (;;) {
+    if (tid == 0) s_item = pop_item(a.hdr->dq_counter, a.hdr->dq_begin);
+    __syncthreads();
+    const int item_idx = s_item;
+    if (item_idx < 0) break;
+    const FwdItem it = a.dq_items[item_idx];
+    const int kvh = it.head / group;
+    const int my_row = wave * 32 + l32;
+    const bool row_ok = my_row < it.q_rows;
+    const int wave_row_lo = it.tile_off + wave * 32;
+    const uint16_t* kbase = a.k + (int64_t)kvh * D;
+    const uint16_t* vbase = a.v + (int64_t)kvh * D;
+
+    bf16x8 qf[KC], dof[KC];
+    float lse_l = INFINITY, dl_l = 0.f;     // rows past the end: P = exp2(-inf) = 0
+    {
+      const int64_t off = (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D + 8 * g;
+#pragma unroll
+      for (int kc = 0; kc < KC; kc++) {
+        u32x4 zq = {0, 0, 0, 0}, zd = {0, 0, 0, 0};
+        if (row_ok) {
+          zq = *reinterpret_cast<const u32x4*>(a.q + off + kc * 16);
+          zd = *reinterpret_cast<const u32x4*>(a.d_o + off + kc * 16);
+        }
+        qf[kc] = as_bf16x8(zq); dof[kc] = as_bf16x8(zd);
+      }
+      if (row_ok) {
+        const int64_t rh = (int64_t)(it.q_start + my_row) * a.n_q_heads + it.head;
+        float l = a.lse[rh];
+        if (l == -INFINITY) l = INFINITY;
+        lse_l = l * kLog2e;
+        dl_l = a.delta[rh] * a.scale;
+      }
+    }
+    f32x16 acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
+
+    TileIter ti;
+    ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
+    auto dma = [&](int buf) {
+      const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
+      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
+      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
+    };
+    DevPair tp = ti.cur;
+    int tc0 = 0;
+    bool have = ti.more;
+    if (have) { dma(0); ti.advance(); }
+    dma_wait();
+    __syncthreads();
+    int buf = 0;
+    while (have) {
+      const DevPair np = ti.cur;
+      const int nc0 = ti.c0;
+      const bool nhave = ti.more;
+      if (nhave) { dma(buf ^ 1); ti.advance(); }
+
+      const unsigned char* tk = lds_k[buf];
+      const unsigned char* tv = lds_v[buf];
+      const bool diag = tp.kind == FCP_KIND_DIAG;
+      if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) { s[rt][r] = 0.f; dp[rt][r] = 0.f; }
+#pragma unroll
+        for (int kc = 0; kc < KC; kc++) {
+#pragma unroll
+          for (int rt = 0; rt < 2; rt++) {
+            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + row_off[kc]);
+            const u32x4 vv = *reinterpret_cast<const u32x4*>(tv + rt * 32 * (D * 2) + row_off[kc]);
+            s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s[rt], 0, 0, 0);
+            dp[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), dof[kc], dp[rt], 0, 0, 0);
+          }
+        }
+        const bool need_mask = diag && tc0 + kFwdTileN - 1 > wave_row_lo;
+        const int limit = it.tile_off + my_row;      // last visible column of a DIAG pair
+#pragma unroll
+        for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rt][r], a.scale_log2, -lse_l));
+            if (need_mask && tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) p = 0.f;
+            s[rt][r] = p * __builtin_fmaf(dp[rt][r], a.scale, -dl_l);
+          }
+#pragma unroll
+        for (int rt = 0; rt < 2; rt++) {
+#pragma unroll
+          for (int j = 0; j < 2; j++) {
+            u32x4 db;
+#pragma unroll
+            for (int i = 0; i < 4; i++) db[i] = pack_bf16(s[rt][8 * j + 2 * i], s[rt][8 * j + 2 * i + 1]);
+            const unsigned char* base = tk + (rt * 32 + 16 * j) * (D * 2);
+#pragma unroll
+            for (int dt = 0; dt < DT; dt++) {
+              const bf16x8 kt = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
+              acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, as_bf16x8(db), acc[dt], 0, 0, 0);
+            }
+          }
+        }
+      }
+      tp = np; tc0 = nc0; have = nhave;
+      dma_wait();
+      __syncthreads();
+      buf ^= 1;
+    }
+    if (row_ok) {
+      float* op = a.dq + (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D;
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
+          *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
+        }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) retire(a.hdr->dq_counter, &a.hdr->dq_done);
 }
 
 // =====================================================================================
@@ -677,7 +856,8 @@ static float resolve_scale(const fcp_problem* p) {
 }
 
 constexpr int kFwdWgPerCu = 2;
-constexpr int kBwdWgPerCu = 1;
+constexpr int kDkdvWgPerCu = 1;   // 8 waves each
+constexpr int kDqWgPerCu = 2;
 
 }  // namespace fcp
 
@@ -687,7 +867,7 @@ extern "C" int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int3
   const int n = cu_count();
   if (n_compute_units) *n_compute_units = n;
   if (fwd_grid) *fwd_grid = n * kFwdWgPerCu;
-  if (bwd_grid) *bwd_grid = n * kBwdWgPerCu;
+  if (bwd_grid) *bwd_grid = n * kDkdvWgPerCu;
   return FCP_OK;
 }
 
@@ -735,7 +915,7 @@ extern "C" int fcp_merge_partials(const fcp_problem* p, const float* o_part, con
   return check_launch("fcp_merge_partials");
 }
 
-extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o, float* dq,
+extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o,
                                   void* workspace, void* stream) {
   int rc = validate_problem(p);
   if (rc) return rc;
@@ -744,15 +924,11 @@ extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const voi
   if (rc) return rc;
   const int64_t n_rh = L.t_q * p->n_q_heads;
   if (n_rh == 0) return FCP_OK;
-  if (!o || !d_o || !dq || !workspace) { set_error("fcp_bwd_preprocess: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (!o || !d_o || !workspace) { set_error("fcp_bwd_preprocess: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   hipStream_t st = (hipStream_t)stream;
   float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + L.off_delta);
   const int o_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
   const int D = p->head_dim;
-  // dQ is accumulated with atomics: clear it (a fill kernel, so the call can sit in a captured graph).
-  const int64_t n4 = n_rh * D / 4;
-  const int zgrid = (int)std::min<int64_t>((n4 + 255) / 256, (int64_t)cu_count() * 8);
-  hipLaunchKernelGGL(zero_kernel, dim3(zgrid), dim3(256), 0, st, reinterpret_cast<f32x4*>(dq), n4);
   const int64_t blocks = (n_rh * (D / 8) + 255) / 256;
   if (D == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, delta, n_rh);
   else hipLaunchKernelGGL(delta_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, delta, n_rh);
@@ -767,20 +943,29 @@ extern "C" int fcp_block_attn_bwd_main(const fcp_problem* p, const void* q, cons
   WsLayout L;
   rc = compute_layout(p, &L);
   if (rc) return rc;
-  if (L.n_bwd_items == 0) return FCP_OK;
+  if (L.n_bwd_items == 0 && L.n_dq_items == 0) return FCP_OK;
   if (!q || !k || !v || !lse || !d_o || !dq || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_main: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   BwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.lse = lse; a.delta = reinterpret_cast<const float*>(ws + L.off_delta); a.dq = dq; a.dk = dk; a.dv = dv;
   a.hdr = reinterpret_cast<WsHeader*>(ws);
+  a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);
   a.deps = reinterpret_cast<const BwdDep*>(ws + L.off_bwd_deps);
   a.items = reinterpret_cast<const BwdItem*>(ws + L.off_bwd_items);
+  a.dq_items = reinterpret_cast<const FwdItem*>(ws + L.off_dq_items);
   a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.scale = resolve_scale(p); a.scale_log2 = a.scale * kLog2e;
-  const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kBwdWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(bwd_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(bwd_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  if (L.n_bwd_items > 0) {
+    const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
+    if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  }
+  if (L.n_dq_items > 0) {
+    const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
+    if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  }
   return check_launch("fcp_block_attn_bwd_main");
 }
 
@@ -793,7 +978,7 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
     set_error("fcp_block_attn_bwd: NULL pointer");
     return FCP_ERR_INVALID_ARG;
   }
-  int rc = fcp_bwd_preprocess(p, o, d_o, dq, workspace, stream);
+  int rc = fcp_bwd_preprocess(p, o, d_o, workspace, stream);
   if (rc) return rc;
   return fcp_block_attn_bwd_main(p, q, k, v, lse, d_o, dq, dk, dv, workspace, stream);
 }

@@ -57,7 +57,7 @@ class DevicePath:
 
 
     def bwd_pre(self):
-        B.fcp_bwd_preprocess(self.problem, self.o, self.d_o, self.dq, self.ws_ptr, self.stream)
+        B.fcp_bwd_preprocess(self.problem, self.o, self.d_o, self.ws_ptr, self.stream)
 
     def bwd_main(self):
         B.fcp_block_attn_bwd_main(self.problem, self.q, self.k, self.v, self.lse, self.d_o,

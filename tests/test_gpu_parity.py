@@ -140,6 +140,6 @@ def test_repeated_calls_reuse_the_workspace():
         outs.append((dp.o.float().cpu().numpy().copy(), dp.dk.cpu().numpy().copy(), dp.dq.cpu().numpy().copy()))
     for o, dk, dq in outs[1:]:
         assert np.array_equal(o, outs[0][0]) and np.array_equal(dk, outs[0][1])
-        assert np.max(np.abs(dq - outs[0][2])) < 1e-4      # atomic order may differ
+        assert np.array_equal(dq, outs[0][2])               # one writer per row, fixed order
     o_ref, _ = orc.worker_fwd(wl.q(), wl.k(), wl.v(), wl.seq_lens, wl.block_size, wl.causal)
     _check("o", outs[-1][0][: o_ref.shape[0]], o_ref)
