@@ -75,11 +75,24 @@ __device__ __forceinline__ int tile_off(int r, int c) { return r * (D * 2) + ((c
 // i of instruction n fills physical chunk i % (D/8) of row n*(1024/(2D)) + i/(D/8) and fetches
 // the logical chunk that the swizzle places there.  Rows >= valid_rows are filled from a zero
 // page.  Completion: s_waitcnt vmcnt(0) by the issuing wave, then a workgroup barrier.
+// The load is issued through inline assembly on purpose: the compiler then does not model it as
+// a write to LDS, so it does not make every later LDS read of the *other* buffer wait for it
+// (it cannot tell run-time-indexed buffers apart).  Ordering is explicit instead: dma_wait()
+// and a barrier before anyone reads what was loaded.  m0 carries the wave-uniform LDS address.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is clobbered on purpose; nothing else here lives in it
+__device__ __forceinline__ void lds_dma16(const unsigned char* gptr, uint32_t lds_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gptr), "s"(m0) : "memory", "m0");
+}
+#pragma clang diagnostic pop
 template <int D, int ROWS, int NWAVES>
 __device__ __forceinline__ void tile_dma(unsigned char* lds_tile, const uint16_t* src, int64_t row_stride,
                                          int valid_rows, const unsigned char* zeros, int wave, int lane) {
   constexpr int CPR = D / 8, RPI = 64 / CPR, NI = ROWS / RPI;
   static_assert(NI % NWAVES == 0, "tile does not split evenly over the waves");
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_tile;
 #pragma unroll
   for (int n = 0; n < NI / NWAVES; n++) {
     const int inst = n * NWAVES + wave;
@@ -87,8 +100,7 @@ __device__ __forceinline__ void tile_dma(unsigned char* lds_tile, const uint16_t
     const int pc = lane % CPR;
     const unsigned char* gp = zeros + pc * 16;
     if (r < valid_rows) gp = reinterpret_cast<const unsigned char*>(src + (int64_t)r * row_stride + ((pc ^ swz<D>(r)) << 3));
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                     (__attribute__((address_space(3))) void*)(lds_tile + inst * 1024), 16, 0, 0);
+    lds_dma16(gp, lds_base + inst * 1024);
   }
 }
 __device__ __forceinline__ void dma_wait() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
@@ -194,7 +206,7 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->fwd_counter, a.hdr->fwd_begin);
     __syncthreads();
-    const int item_idx = s_item;
+    const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
     const FwdItem it = a.items[item_idx];
     const int kvh = it.head / group;
@@ -248,18 +260,33 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
       const bool diag = tp.kind == FCP_KIND_DIAG;
       // a wave whose rows all lie above this tile's first column has nothing visible in it
       if (!(diag && tc0 > wave_row_lo + 31)) {
-        // ---- S^T = K Q^T  (two 32-row tiles of KV)
+        // ---- S^T = K Q^T  (two 32-row tiles of KV).  The K fragments of k-chunk kc+1 are requested
+        // before the MFMAs of chunk kc are issued, so the LDS latency hides behind them.
         f32x16 s[2];
 #pragma unroll
         for (int rt = 0; rt < 2; rt++)
 #pragma unroll
           for (int r = 0; r < 16; r++) s[rt][r] = 0.f;
+        {
+          constexpr int PF = 2;                      // stages (of two MFMAs) requested ahead
+          u32x4 kfr[PF + 1][2];
 #pragma unroll
-        for (int kc = 0; kc < KC; kc++) {
+          for (int p = 0; p < PF; p++)
 #pragma unroll
-          for (int rt = 0; rt < 2; rt++) {
-            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[kc]);
-            s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s[rt], 0, 0, 0);
+            for (int rt = 0; rt < 2; rt++)
+              kfr[p][rt] = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[p]);
+#pragma unroll
+          for (int kc = 0; kc < KC; kc++) {
+            if (kc + PF < KC) {
+#pragma unroll
+              for (int rt = 0; rt < 2; rt++)
+                kfr[(kc + PF) % (PF + 1)][rt] = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[kc + PF]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rt = 0; rt < 2; rt++)
+              s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kfr[kc % (PF + 1)][rt]), qf[kc], s[rt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
         // ---- mask (only tiles that touch the diagonal or the ragged end)
@@ -304,22 +331,31 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
             rs += p;
           }
         l_run += rs;
-        // ---- O^T += V^T P^T ; P^T's accumulator registers are its B operand
+        // ---- O^T += V^T P^T ; P^T's accumulator registers are its B operand.  The V^T fragment of
+        // the next MFMA is requested before the current MFMA is issued.
+        {
+          u32x4 pb[4];
 #pragma unroll
-        for (int rt = 0; rt < 2; rt++) {
+          for (int rt = 0; rt < 2; rt++)
 #pragma unroll
-          for (int j = 0; j < 2; j++) {
-            u32x4 pb;
-            pb[0] = pack_bf16(s[rt][8 * j + 0], s[rt][8 * j + 1]);
-            pb[1] = pack_bf16(s[rt][8 * j + 2], s[rt][8 * j + 3]);
-            pb[2] = pack_bf16(s[rt][8 * j + 4], s[rt][8 * j + 5]);
-            pb[3] = pack_bf16(s[rt][8 * j + 6], s[rt][8 * j + 7]);
-            const unsigned char* base = tv + (rt * 32 + 16 * j) * (D * 2);
+            for (int j = 0; j < 2; j++)
 #pragma unroll
-            for (int dt = 0; dt < DT; dt++) {
-              const bf16x8 vt = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
-              o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, as_bf16x8(pb), o[dt], 0, 0, 0);
-            }
+              for (int i = 0; i < 4; i++) pb[rt * 2 + j][i] = pack_bf16(s[rt][8 * j + 2 * i], s[rt][8 * j + 2 * i + 1]);
+          constexpr int PF = 3;                      // MFMAs requested ahead
+          constexpr int NU = 4 * DT;                 // u = (rt, j, dt)
+          bf16x8 vfr[PF + 1];
+          auto fetch = [&](int u) {
+            const unsigned char* base = tv + 16 * (u / DT) * (D * 2);
+            return lds_tr_pair(base + tr_lo[u % DT], base + tr_hi[u % DT]);
+          };
+#pragma unroll
+          for (int p = 0; p < PF; p++) vfr[p] = fetch(p);
+#pragma unroll
+          for (int u = 0; u < NU; u++) {
+            if (u + PF < NU) vfr[(u + PF) % (PF + 1)] = fetch(u + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            o[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[u % (PF + 1)], as_bf16x8(pb[u / DT]), o[u % DT], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
@@ -490,8 +526,9 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
   constexpr int TB = tile_bytes<D>(32);
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_q[3][TB];
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_do[3][TB];
+  // Each buffer holds [Q tile | dO tile].  Which of the two a wave reads depends on its role;
+  // that choice is folded into the per-lane offsets, so an LDS address is "buffer base + VGPR".
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_t[3][2 * TB];
   __shared__ __attribute__((aligned(16))) unsigned char lds_p[2][4][4096];   // [buffer][kv sub-tile][q4][lane] float4
   __shared__ __attribute__((aligned(16))) float lds_lse[3][32];
   __shared__ __attribute__((aligned(16))) float lds_dl[3][32];
@@ -508,16 +545,17 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
   int tr_lo[DT], tr_hi[DT], row_off[KC];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++) {
-    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    // phase 2 reads the tile of the other role: dO^T for role 0, Q^T for role 1
+    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
+    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
   }
 #pragma unroll
-  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g);
+  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g) + (role ? TB : 0);   // phase 1: Q (role 0) or dO (role 1)
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->bwd_counter, a.hdr->bwd_begin);
     __syncthreads();
-    const int item_idx = s_item;
+    const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
     const BwdItem it = a.items[item_idx];
     const int my_kv = sub * 32 + l32;                  // KV row inside the tile
@@ -549,7 +587,7 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
     auto dma = [&](int buf) {
       const int head = it.kv_head * group + si.hh;
       const uint16_t* src = (role ? a.d_o : a.q) + (int64_t)(si.cur.q_start + si.q0) * q_row_stride + (int64_t)head * D;
-      tile_dma<D, 32, 4>(role ? lds_do[buf] : lds_q[buf], src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane);
+      tile_dma<D, 32, 4>(lds_t[buf] + (role ? TB : 0), src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane);
       if (tid < 32) {
         const int r = si.q0 + tid;
         float l = INFINITY, dl = 0.f;      // rows past the end get P = exp2(-inf) = 0
@@ -581,8 +619,7 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
     int t = 0;          // step counter modulo 3 (tile buffers) and parity (P buffers)
     int pbuf = 0;
     while (have) {
-      const unsigned char* tq = lds_q[t];
-      const unsigned char* tdo = lds_do[t];
+      const unsigned char* tt = lds_t[t];
       const bool diag = td.kind == FCP_KIND_DIAG;
       const int kv_in_blk = it.tile_off + my_kv;
       unsigned char* pslot = lds_p[pbuf][sub] + lane * 16;
@@ -591,10 +628,9 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
       for (int r = 0; r < 16; r++) s[r] = 0.f;
       // ---- phase 1: S = Q K^T (role 0) or dP = dO V^T (role 1); rows = query, cols = KV
       {
-        const unsigned char* ta = role ? tdo : tq;
 #pragma unroll
         for (int kc = 0; kc < KC; kc++) {
-          const u32x4 aa = *reinterpret_cast<const u32x4*>(ta + row_off[kc]);
+          const u32x4 aa = *reinterpret_cast<const u32x4*>(tt + row_off[kc]);
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aa), bfr[kc], s, 0, 0, 0);
         }
       }
@@ -635,7 +671,6 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
       // dV^T += dO^T P (role 0) or dK^T += Q^T dS (role 1):
       // k-slot (g, i) of chunk j = query 16j + 8(i/4) + 4g + i%4
       {
-        const unsigned char* tt = role ? tq : tdo;
 #pragma unroll
         for (int j = 0; j < 2; j++) {
           u32x4 b;
@@ -708,7 +743,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->dq_counter, a.hdr->dq_begin);
     __syncthreads();
-    const int item_idx = s_item;
+    const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
     const FwdItem it = a.dq_items[item_idx];
     const int kvh = it.head / group;
@@ -769,38 +804,32 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
       const unsigned char* tv = lds_v[buf];
       const bool diag = tp.kind == FCP_KIND_DIAG;
       if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
-        f32x16 s[2], dp[2];
-#pragma unroll
-        for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) { s[rt][r] = 0.f; dp[rt][r] = 0.f; }
-#pragma unroll
-        for (int kc = 0; kc < KC; kc++) {
-#pragma unroll
-          for (int rt = 0; rt < 2; rt++) {
-            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + row_off[kc]);
-            const u32x4 vv = *reinterpret_cast<const u32x4*>(tv + rt * 32 * (D * 2) + row_off[kc]);
-            s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s[rt], 0, 0, 0);
-            dp[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), dof[kc], dp[rt], 0, 0, 0);
-          }
-        }
         const bool need_mask = diag && tc0 + kFwdTileN - 1 > wave_row_lo;
         const int limit = it.tile_off + my_row;      // last visible column of a DIAG pair
-#pragma unroll
-        for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rt][r], a.scale_log2, -lse_l));
-            if (need_mask && tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) p = 0.f;
-            s[rt][r] = p * __builtin_fmaf(dp[rt][r], a.scale, -dl_l);
-          }
+        // the two 32-row halves of the KV tile one after the other: half the live accumulators
 #pragma unroll
         for (int rt = 0; rt < 2; rt++) {
+          f32x16 s, dp;
+#pragma unroll
+          for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+          for (int kc = 0; kc < KC; kc++) {
+            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + row_off[kc]);
+            const u32x4 vv = *reinterpret_cast<const u32x4*>(tv + rt * 32 * (D * 2) + row_off[kc]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), dof[kc], dp, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], a.scale_log2, -lse_l));
+            if (need_mask && tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) p = 0.f;
+            s[r] = p * __builtin_fmaf(dp[r], a.scale, -dl_l);
+          }
 #pragma unroll
           for (int j = 0; j < 2; j++) {
             u32x4 db;
 #pragma unroll
-            for (int i = 0; i < 4; i++) db[i] = pack_bf16(s[rt][8 * j + 2 * i], s[rt][8 * j + 2 * i + 1]);
+            for (int i = 0; i < 4; i++) db[i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
             const unsigned char* base = tk + (rt * 32 + 16 * j) * (D * 2);
 #pragma unroll
             for (int dt = 0; dt < DT; dt++) {
