@@ -3,7 +3,7 @@
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM:
 forward partials (fcp_block_attn_fwd) -> merge (fcp_merge_partials) -> backward preprocess
-(fcp_bwd_preprocess) -> backward (fcp_block_attn_bwd_main).  The default workload is the
+(fcp_bwd_preprocess) -> dK/dV (fcp_block_attn_bwd_dkdv) -> dQ (fcp_block_attn_bwd_dq).  The default workload is the
 packed variable-length training step (64K tokens, 1024-token blocks, GQA 32/8, d = 128, bf16).
 
 Prints ONE JSON line: whole-step throughput in causal-adjusted TFLOP/s, the roofline of the
@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload: 5 = training step (default), 2/3/4 = forward only")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): under rocprofv3 --pmc "
+                         "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -106,7 +109,7 @@ def main():
 
     stages = [("fwd", dp.fwd), ("merge", dp.merge)]
     if backward:
-        stages += [("bwd_pre", dp.bwd_pre), ("bwd", dp.bwd_main)]
+        stages += [("bwd_pre", dp.bwd_pre), ("bwd_dkdv", dp.bwd_dkdv), ("bwd_dq", dp.bwd_dq)]
 
     def step(events=None):
         for i, (_, fn) in enumerate(stages):
@@ -116,6 +119,13 @@ def main():
             if events is not None:
                 events[i][1].record(stream)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize(dev)
+        dst.copy_(src)
+        torch.cuda.synchronize(dev)
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize(dev)
@@ -132,10 +142,16 @@ def main():
     for i, (name, _) in enumerate(stages):
         stage_ms[name] = sum(evs[s][i][0].elapsed_time(evs[s][i][1]) for s in range(args.steps)) / args.steps
 
-    # dominant kernel: the contraction kernel with the larger average duration
-    dom = "bwd" if backward and stage_ms["bwd"] >= stage_ms["fwd"] else "fwd"
-    dom_flops = f_bwd if dom == "bwd" else f_fwd
-    achieved = dom_flops / (stage_ms[dom] * 1e-3) / 1e12
+    # Each timed stage except bwd_pre is exactly one kernel launch.  Algorithmic FLOPs per launch:
+    # forward 2 contractions (4 d per unmasked entry and head), dK/dV kernel 4 (S, dP, dV, dK: 8 d),
+    # dQ kernel 3 (S, dP, dQ: 6 d; S and dP are recomputed there instead of accumulating dQ with
+    # atomics, so the backward executes 14 d per entry for an algorithmic 10 d).
+    unit = wl.head_dim * wl.n_q_heads * nnz
+    kernel_flops = {"fwd": 4 * unit, "bwd_dkdv": 8 * unit, "bwd_dq": 6 * unit}
+    kernel_name = {"fwd": "fwd_kernel", "bwd_dkdv": "dkdv_kernel", "bwd_dq": "dq_kernel"}
+    cands = [k for k in kernel_flops if k in stage_ms]
+    dom = max(cands, key=lambda k: stage_ms[k])
+    achieved = kernel_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
     p = dp.problem
     merge_bytes = (p.n_slot_rows * wl.n_q_heads * (wl.head_dim * 4 + 4)
                    + p.t_q * wl.n_q_heads * (wl.head_dim * (4 if backward else 2) + 4))
@@ -157,14 +173,13 @@ def main():
         },
         "frac_of_bf16_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-        "stage_tflops": {"fwd": round(f_fwd / stage_ms["fwd"] / 1e9, 2),
-                         **({"bwd": round(f_bwd / stage_ms["bwd"] / 1e9, 2)} if backward else {})},
+        "kernel_tflops": {k: round(kernel_flops[k] / stage_ms[k] / 1e9, 2) for k in cands},
         "merge_gbs": round(merge_bytes / stage_ms["merge"] / 1e6, 1),
         "roofline": {
-            "kernel": "bwd_kernel" if dom == "bwd" else "fwd_kernel",
+            "kernel": kernel_name[dom],
             "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name[dom])),
             "avg_launch_ms": round(stage_ms[dom], 4),
         },
         "grid": info, "setup_s": round(setup_s, 2),

@@ -163,18 +163,22 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
                        float* dq, float* dk, float* dv, void* workspace, void* stream);
 
 /*
- * The two halves of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
- * fcp_bwd_preprocess: writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
- * fcp_block_attn_bwd_main: the contraction kernels (dK/dV KV-stationary, dQ query-stationary);
- * needs fcp_bwd_preprocess to have run on the same workspace (same stream, or ordered after it)
- * with the same o / d_o.
+ * The three stages of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
+ * fcp_bwd_preprocess:      writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
+ * fcp_block_attn_bwd_dkdv: KV-stationary kernel, writes dk and dv.
+ * fcp_block_attn_bwd_dq:   query-stationary kernel, writes dq.
+ * The last two need fcp_bwd_preprocess to have run on the same workspace (same stream, or ordered
+ * after it) with the same o / d_o, and are independent of each other.
  * Arguments, layouts and errors as for fcp_block_attn_bwd.
  */
 int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o,
                        void* workspace, void* stream);
-int fcp_block_attn_bwd_main(const fcp_problem* p, const void* q, const void* k, const void* v,
+int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
                             const float* lse, const void* d_o,
-                            float* dq, float* dk, float* dv, void* workspace, void* stream);
+                            float* dk, float* dv, void* workspace, void* stream);
+int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
+                          const float* lse, const void* d_o,
+                          float* dq, void* workspace, void* stream);
 
 /* Text of the calling thread's last error ("" if none).  The pointer stays valid until the
  * thread's next failing call. */

@@ -26,7 +26,7 @@ FCP_FLAG_O_F32 = 1
 
 EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd",
-    "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_main",
+    "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_last_error", "fcp_device_info",
 )
 
@@ -62,7 +62,8 @@ def _load():
     lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
     lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 4
-    lib.fcp_block_attn_bwd_main.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 10
+    lib.fcp_block_attn_bwd_dkdv.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 9
+    lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 8
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
     for name in EXPORTS:
@@ -176,9 +177,14 @@ def fcp_bwd_preprocess(problem: Problem, o, d_o, workspace, stream=None):
     _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(d_o), _ptr(workspace), _stream(stream)))
 
 
-def fcp_block_attn_bwd_main(problem: Problem, q, k, v, lse, d_o, dq, dk, dv, workspace, stream=None):
-    _check(_lib.fcp_block_attn_bwd_main(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
-                                        _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
+def fcp_block_attn_bwd_dkdv(problem: Problem, q, k, v, lse, d_o, dk, dv, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_dkdv(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
+                                        _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_bwd_dq(problem: Problem, q, k, v, lse, d_o, dq, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_dq(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
+                                      _ptr(dq), _ptr(workspace), _stream(stream)))
 
 
 def fcp_device_info():

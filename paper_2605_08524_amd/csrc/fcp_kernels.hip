@@ -964,38 +964,56 @@ extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const voi
   return check_launch("fcp_bwd_preprocess");
 }
 
-extern "C" int fcp_block_attn_bwd_main(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                       const float* lse, const void* d_o,
-                                       float* dq, float* dk, float* dv, void* workspace, void* stream) {
+static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* workspace) {
   int rc = validate_problem(p);
   if (rc) return rc;
-  WsLayout L;
-  rc = compute_layout(p, &L);
+  rc = compute_layout(p, L);
   if (rc) return rc;
-  if (L.n_bwd_items == 0 && L.n_dq_items == 0) return FCP_OK;
-  if (!q || !k || !v || !lse || !d_o || !dq || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_main: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   unsigned char* ws = static_cast<unsigned char*>(workspace);
+  a->hdr = reinterpret_cast<WsHeader*>(ws);
+  a->delta = reinterpret_cast<const float*>(ws + L->off_delta);
+  a->pairs = reinterpret_cast<const DevPair*>(ws + L->off_pairs);
+  a->deps = reinterpret_cast<const BwdDep*>(ws + L->off_bwd_deps);
+  a->items = reinterpret_cast<const BwdItem*>(ws + L->off_bwd_items);
+  a->dq_items = reinterpret_cast<const FwdItem*>(ws + L->off_dq_items);
+  a->n_q_heads = p->n_q_heads; a->n_kv_heads = p->n_kv_heads;
+  a->scale = resolve_scale(p); a->scale_log2 = a->scale * kLog2e;
+  a->dq = nullptr; a->dk = nullptr; a->dv = nullptr;
+  return FCP_OK;
+}
+
+extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                       const float* lse, const void* d_o,
+                                       float* dk, float* dv, void* workspace, void* stream) {
+  WsLayout L;
   BwdArgs a;
+  int rc = fill_bwd_args(p, &L, &a, workspace);
+  if (rc) return rc;
+  if (L.n_bwd_items == 0) return FCP_OK;
+  if (!q || !k || !v || !lse || !d_o || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_dkdv: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
-  a.lse = lse; a.delta = reinterpret_cast<const float*>(ws + L.off_delta); a.dq = dq; a.dk = dk; a.dv = dv;
-  a.hdr = reinterpret_cast<WsHeader*>(ws);
-  a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);
-  a.deps = reinterpret_cast<const BwdDep*>(ws + L.off_bwd_deps);
-  a.items = reinterpret_cast<const BwdItem*>(ws + L.off_bwd_items);
-  a.dq_items = reinterpret_cast<const FwdItem*>(ws + L.off_dq_items);
-  a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
-  a.scale = resolve_scale(p); a.scale_log2 = a.scale * kLog2e;
-  if (L.n_bwd_items > 0) {
-    const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
-    if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  }
-  if (L.n_dq_items > 0) {
-    const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
-    if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
-  }
-  return check_launch("fcp_block_attn_bwd_main");
+  a.lse = lse; a.dk = dk; a.dv = dv;
+  const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
+  if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  return check_launch("fcp_block_attn_bwd_dkdv");
+}
+
+extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                     const float* lse, const void* d_o,
+                                     float* dq, void* workspace, void* stream) {
+  WsLayout L;
+  BwdArgs a;
+  int rc = fill_bwd_args(p, &L, &a, workspace);
+  if (rc) return rc;
+  if (L.n_dq_items == 0) return FCP_OK;
+  if (!q || !k || !v || !lse || !d_o || !dq || !workspace) { set_error("fcp_block_attn_bwd_dq: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
+  a.lse = lse; a.dq = dq;
+  const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
+  if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  return check_launch("fcp_block_attn_bwd_dq");
 }
 
 extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
@@ -1009,5 +1027,7 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
   }
   int rc = fcp_bwd_preprocess(p, o, d_o, workspace, stream);
   if (rc) return rc;
-  return fcp_block_attn_bwd_main(p, q, k, v, lse, d_o, dq, dk, dv, workspace, stream);
+  rc = fcp_block_attn_bwd_dkdv(p, q, k, v, lse, d_o, dk, dv, workspace, stream);
+  if (rc) return rc;
+  return fcp_block_attn_bwd_dq(p, q, k, v, lse, d_o, dq, workspace, stream);
 }
