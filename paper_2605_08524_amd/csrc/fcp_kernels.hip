@@ -57,6 +57,22 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const unsigned char* lo, const uns
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
+// LDS accesses through 32-bit LDS addresses kept in registers: a tile buffer switch is then one
+// add per address (in place) and row / tile offsets fold into the instruction's immediate field.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
+}
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr) {
+  return *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)addr;
+}
+__device__ __forceinline__ bf16x8 lds_tr_pair_at(uint32_t lo, uint32_t hi) {
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)lo);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)hi);
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, c);
+}
+
 // Byte offset of 16-byte chunk c of row r in an LDS tile.  Rows are unpadded (D*2 bytes) because
 // tiles are filled by LDS-DMA loads that write 1 KB of consecutive LDS per wave instruction; the
 // chunk index is XOR-swizzled with the row so that both access patterns are conflict free for
@@ -87,12 +103,50 @@ __device__ __forceinline__ void lds_dma16(const unsigned char* gptr, uint32_t ld
                :: "v"(gptr), "s"(m0) : "memory", "m0");
 }
 #pragma clang diagnostic pop
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void lds_dma16_s(const unsigned char* sbase, uint32_t voff, uint32_t lds_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+  const uint64_t b = reinterpret_cast<uint64_t>(sbase);       // wave-uniform by construction
+  // readfirstlane returns a signed int: widen through uint32_t, or the low half sign-extends
+  // into the high half of the address.
+  const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
+  const uint64_t sb = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
+  // s_nop 4: a vector-memory instruction may read an SGPR only 5 wait states after a scalar or
+  // v_readfirstlane write to it; the compiler's hazard pass does not look inside inline assembly,
+  // and the base in %1 is typically produced right before this statement.  (Also covers m0.)
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sb), "s"(m0) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+// Byte offset, from the first row of a 1 KB load instruction, of the chunk that lane `lane` of
+// wave `wave` fetches.  Instruction n*NWAVES + wave covers rows that differ from wave's first
+// instruction by a multiple of 16, the period of the swizzle, so the offset is one per-lane
+// constant for the whole kernel.
+template <int D>
+__device__ __forceinline__ uint32_t dma_lane_offset(int wave, int lane, int64_t row_stride) {
+  constexpr int CPR = D / 8, RPI = 64 / CPR;
+  const int r = wave * RPI + lane / CPR, pc = lane % CPR;
+  return (uint32_t)((lane / CPR) * row_stride * 2 + ((pc ^ swz<D>(r)) << 4));
+}
 template <int D, int ROWS, int NWAVES>
 __device__ __forceinline__ void tile_dma(unsigned char* lds_tile, const uint16_t* src, int64_t row_stride,
-                                         int valid_rows, const unsigned char* zeros, int wave, int lane) {
+                                         int valid_rows, const unsigned char* zeros, int wave, int lane,
+                                         uint32_t lane_off) {
   constexpr int CPR = D / 8, RPI = 64 / CPR, NI = ROWS / RPI;
   static_assert(NI % NWAVES == 0, "tile does not split evenly over the waves");
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_tile;
+  if (valid_rows >= ROWS) {
+    // whole tile in range (wave-uniform): scalar base per instruction + the per-lane constant
+#pragma unroll
+    for (int n = 0; n < NI / NWAVES; n++) {
+      const int inst = n * NWAVES + wave;
+      lds_dma16_s(reinterpret_cast<const unsigned char*>(src + (int64_t)inst * RPI * row_stride), lane_off,
+                  lds_base + inst * 1024);
+    }
+    return;
+  }
 #pragma unroll
   for (int n = 0; n < NI / NWAVES; n++) {
     const int inst = n * NWAVES + wave;
@@ -110,7 +164,8 @@ template <int D> constexpr int tile_bytes(int rows) { return rows * D * 2; }
 // Pop one item index from the eight XCD queues, own queue first, then stealing.  Returns -1
 // when every queue is dry.  Every call terminates: each queue is probed at most once.
 __device__ __forceinline__ int pop_item(int32_t* counter, const int32_t* begin) {
-  const int home = blockIdx.x % kNumXcd;
+  // The XCD this workgroup actually runs on: hardware register XCC_ID (id 20), bits [3:0].
+  const int home = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kNumXcd - 1);
   for (int t = 0; t < kNumXcd; t++) {
     const int q = (home + t) % kNumXcd;
     const int n = begin[q + 1] - begin[q];
@@ -186,22 +241,35 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds_v[2][TB];
   __shared__ int s_item;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;     // elements
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
   const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  const uint32_t dma_off = dma_lane_offset<D>(wave, lane, kv_row_stride);
   // transpose-read pattern inside a 16-lane group: row tr_row, 4 columns from tr_col
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  int tr_lo[DT], tr_hi[DT], kk_off[KC];   // swizzled offsets; the swizzle has period 16 in the row
+  // Per-lane LDS addresses into the CURRENT buffer (the swizzle has period 16 in the row, so
+  // rows +16 / +32 are plain immediate offsets); switched in place after every tile.
+  uint32_t tr_lo[DT], tr_hi[DT], kk_off[KC];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++) {
-    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_lo[dt] = lds_addr(lds_v[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = lds_addr(lds_v[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
   }
 #pragma unroll
-  for (int kc = 0; kc < KC; kc++) kk_off[kc] = tile_off<D>(l32, 2 * kc + g);
+  for (int kc = 0; kc < KC; kc++) kk_off[kc] = lds_addr(lds_k[0]) + tile_off<D>(l32, 2 * kc + g);
+  int buf = 0;                              // buffer the addresses above point into
+  auto switch_buffer = [&]() {
+    const int step = buf ? -TB : TB;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += step; tr_hi[dt] += step; }
+#pragma unroll
+    for (int kc = 0; kc < KC; kc++) kk_off[kc] += step;
+    buf ^= 1;
+  };
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->fwd_counter, a.hdr->fwd_begin);
@@ -238,16 +306,15 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
     ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
     auto dma = [&](int buf) {
       const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
-      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
-      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
+      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
     };
     DevPair tp = ti.cur;              // the tile being computed
     int tc0 = 0;
     bool have = ti.more;              // an empty slot yields O = 0, LSE = -inf
-    if (have) { dma(0); ti.advance(); }
+    if (have) { dma(buf); ti.advance(); }
     dma_wait();
     __syncthreads();
-    int buf = 0;
     while (have) {
       // next tile into the other buffer (its readers finished before the last barrier)
       const DevPair np = ti.cur;
@@ -255,8 +322,6 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
       const bool nhave = ti.more;
       if (nhave) { dma(buf ^ 1); ti.advance(); }
 
-      const unsigned char* tk = lds_k[buf];
-      const unsigned char* tv = lds_v[buf];
       const bool diag = tp.kind == FCP_KIND_DIAG;
       // a wave whose rows all lie above this tile's first column has nothing visible in it
       if (!(diag && tc0 > wave_row_lo + 31)) {
@@ -274,13 +339,13 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
           for (int p = 0; p < PF; p++)
 #pragma unroll
             for (int rt = 0; rt < 2; rt++)
-              kfr[p][rt] = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[p]);
+              kfr[p][rt] = lds_read16(kk_off[p] + rt * 32 * (D * 2));
 #pragma unroll
           for (int kc = 0; kc < KC; kc++) {
             if (kc + PF < KC) {
 #pragma unroll
               for (int rt = 0; rt < 2; rt++)
-                kfr[(kc + PF) % (PF + 1)][rt] = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + kk_off[kc + PF]);
+                kfr[(kc + PF) % (PF + 1)][rt] = lds_read16(kk_off[kc + PF] + rt * 32 * (D * 2));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -345,8 +410,8 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
           constexpr int NU = 4 * DT;                 // u = (rt, j, dt)
           bf16x8 vfr[PF + 1];
           auto fetch = [&](int u) {
-            const unsigned char* base = tv + 16 * (u / DT) * (D * 2);
-            return lds_tr_pair(base + tr_lo[u % DT], base + tr_hi[u % DT]);
+            const uint32_t rows = 16 * (u / DT) * (D * 2);
+            return lds_tr_pair_at(tr_lo[u % DT] + rows, tr_hi[u % DT] + rows);
           };
 #pragma unroll
           for (int p = 0; p < PF; p++) vfr[p] = fetch(p);
@@ -362,7 +427,7 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
       tp = np; tc0 = nc0; have = nhave;
       dma_wait();
       __syncthreads();
-      buf ^= 1;
+      switch_buffer();
     }
 
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
@@ -401,34 +466,65 @@ template <int D>
 __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
   constexpr int LPE = D / 4;            // lanes per entry
   constexpr int EPP = 256 / LPE;        // entries per pass
+  constexpr int U = 4;                  // entries in flight per thread (independent loads)
   const MergeItem it = a.items[blockIdx.x];
   const int sub = threadIdx.x / LPE, ln = threadIdx.x % LPE;
-  for (int e = sub; e < it.n_rh; e += EPP) {
-    const int64_t in_off = it.rh_off + e;
-    float mx = -INFINITY;
-    for (int s = 0; s < it.n_slots; s++)
-      mx = fmaxf(mx, a.lse_part[(int64_t)a.slot_rh[it.slot_begin + s] + in_off]);
-    const float m_use = (mx == -INFINITY) ? 0.f : mx;
-    float tot = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int e0 = sub; e0 < it.n_rh; e0 += EPP * U) {
+    float mx[U], tot[U];
+    f32x4 acc[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      ok[u] = e0 + u * EPP < it.n_rh;
+      mx[u] = -INFINITY; tot[u] = 0.f;
+      acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (it.n_slots > 1) {
+      for (int s = 0; s < it.n_slots; s++) {
+        const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
+#pragma unroll
+        for (int u = 0; u < U; u++)
+          if (ok[u]) mx[u] = fmaxf(mx[u], a.lse_part[base + u * EPP]);
+      }
+    }
     for (int s = 0; s < it.n_slots; s++) {
-      const int64_t rh = (int64_t)a.slot_rh[it.slot_begin + s] + in_off;
-      const float w = __expf(a.lse_part[rh] - m_use);
-      const f32x4 x = *reinterpret_cast<const f32x4*>(a.o_part + rh * D + ln * 4);
-      tot += w;
-      // an empty partial carries weight 0; its payload must not leak through (0 * NaN)
-      if (w > 0.f) acc += w * x;
+      const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
+      float l[U];
+      f32x4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        l[u] = -INFINITY;
+        x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (ok[u]) {
+          l[u] = a.lse_part[base + u * EPP];
+          x[u] = *reinterpret_cast<const f32x4*>(a.o_part + (base + u * EPP) * D + ln * 4);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (it.n_slots == 1) mx[u] = l[u];                       // a single partial is its own maximum
+        const float m_use = (mx[u] == -INFINITY) ? 0.f : mx[u];
+        const float w = __expf(l[u] - m_use);
+        tot[u] += w;
+        // an empty partial carries weight 0; its payload must not leak through (0 * NaN)
+        if (w > 0.f) acc[u] += w * x[u];
+      }
     }
-    const float inv = tot > 0.f ? 1.0f / tot : 0.f;
-    acc *= inv;
-    const int64_t out = (int64_t)it.out_rh + e;
-    if (a.o_is_f32) {
-      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.o) + out * D + ln * 4) = acc;
-    } else {
-      u32x2 h = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
-      *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.o) + out * D + ln * 4) = h;
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      if (!ok[u]) continue;
+      const float m_use = (mx[u] == -INFINITY) ? 0.f : mx[u];
+      const float inv = tot[u] > 0.f ? 1.0f / tot[u] : 0.f;
+      const f32x4 r = acc[u] * inv;
+      const int64_t out = (int64_t)it.out_rh + e0 + u * EPP;
+      if (a.o_is_f32) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.o) + out * D + ln * 4) = r;
+      } else {
+        u32x2 h = {pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3])};
+        *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.o) + out * D + ln * 4) = h;
+      }
+      if (ln == 0) a.lse[out] = tot[u] > 0.f ? m_use + __logf(tot[u]) : -INFINITY;
     }
-    if (ln == 0) a.lse[out] = tot > 0.f ? m_use + __logf(tot) : -INFINITY;
   }
 }
 
@@ -534,23 +630,36 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(16))) float lds_dl[3][32];
   __shared__ int s_item;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int sub = wave & 3, role = wave >> 2;
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
   const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  const uint32_t dma_off = dma_lane_offset<D>(sub, lane, q_row_stride);
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  int tr_lo[DT], tr_hi[DT], row_off[KC];
+  // absolute LDS addresses into the buffer of the CURRENT step, advanced in place every step
+  uint32_t tr_lo[DT], tr_hi[DT], row_off[KC];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++) {
     // phase 2 reads the tile of the other role: dO^T for role 0, Q^T for role 1
-    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
-    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
+    tr_lo[dt] = lds_addr(lds_t[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
+    tr_hi[dt] = lds_addr(lds_t[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
   }
 #pragma unroll
-  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g) + (role ? TB : 0);   // phase 1: Q (role 0) or dO (role 1)
+  for (int kc = 0; kc < KC; kc++)   // phase 1: Q (role 0) or dO (role 1)
+    row_off[kc] = lds_addr(lds_t[0]) + tile_off<D>(l32, 2 * kc + g) + (role ? TB : 0);
+  int t = 0;            // step counter modulo 3: the tile buffer the addresses above point into
+  auto next_buffer = [&]() {
+    const int step = (t == 2) ? -4 * TB : 2 * TB;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += step; tr_hi[dt] += step; }
+#pragma unroll
+    for (int kc = 0; kc < KC; kc++) row_off[kc] += step;
+    t = (t == 2) ? 0 : t + 1;
+  };
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->bwd_counter, a.hdr->bwd_begin);
@@ -587,7 +696,7 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
     auto dma = [&](int buf) {
       const int head = it.kv_head * group + si.hh;
       const uint16_t* src = (role ? a.d_o : a.q) + (int64_t)(si.cur.q_start + si.q0) * q_row_stride + (int64_t)head * D;
-      tile_dma<D, 32, 4>(lds_t[buf] + (role ? TB : 0), src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane);
+      tile_dma<D, 32, 4>(lds_t[buf] + (role ? TB : 0), src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane, dma_off);
       if (tid < 32) {
         const int r = si.q0 + tid;
         float l = INFINITY, dl = 0.f;      // rows past the end get P = exp2(-inf) = 0
@@ -610,16 +719,15 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
     int nq0 = 0;
     bool nhave = false;
     if (have) {
-      dma(0); dma_wait(); publish_scalars(0);
+      const int t1 = (t == 2) ? 0 : t + 1;
+      dma(t); dma_wait(); publish_scalars(t);
       si.advance();
       nd = si.cur; nq0 = si.q0; nhave = si.more;
-      if (nhave) { dma(1); dma_wait(); publish_scalars(1); si.advance(); }
+      if (nhave) { dma(t1); dma_wait(); publish_scalars(t1); si.advance(); }
     }
     __syncthreads();
-    int t = 0;          // step counter modulo 3 (tile buffers) and parity (P buffers)
-    int pbuf = 0;
+    int pbuf = 0;       // parity of the P hand-over buffer
     while (have) {
-      const unsigned char* tt = lds_t[t];
       const bool diag = td.kind == FCP_KIND_DIAG;
       const int kv_in_blk = it.tile_off + my_kv;
       unsigned char* pslot = lds_p[pbuf][sub] + lane * 16;
@@ -630,7 +738,7 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
       {
 #pragma unroll
         for (int kc = 0; kc < KC; kc++) {
-          const u32x4 aa = *reinterpret_cast<const u32x4*>(tt + row_off[kc]);
+          const u32x4 aa = lds_read16(row_off[kc]);
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aa), bfr[kc], s, 0, 0, 0);
         }
       }
@@ -639,14 +747,19 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
           const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lds_lse[t][8 * q4 + 4 * g]);
-          f32x4 p4;
 #pragma unroll
-          for (int i = 0; i < 4; i++) {
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * q4 + i], a.scale_log2, -lse4[i]));
-            if (diag && kv_in_blk > tq0 + 8 * q4 + 4 * g + i) p = 0.f;
-            s[4 * q4 + i] = p;
-            p4[i] = p;
-          }
+          for (int i = 0; i < 4; i++)
+            s[4 * q4 + i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * q4 + i], a.scale_log2, -lse4[i]));
+        }
+        // only steps that straddle the diagonal need the mask (wave-uniform test)
+        if (diag && it.tile_off + sub * 32 + 31 > tq0) {
+#pragma unroll
+          for (int r = 0; r < 16; r++)
+            if (kv_in_blk > tq0 + 8 * (r >> 2) + 4 * g + (r & 3)) s[r] = 0.f;
+        }
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x4 p4 = {s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]};
           *reinterpret_cast<f32x4*>(pslot + q4 * 1024) = p4;
         }
       }
@@ -676,17 +789,17 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
           u32x4 b;
 #pragma unroll
           for (int i = 0; i < 4; i++) b[i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
-          const unsigned char* base = tt + 16 * j * (D * 2);
+          const uint32_t rows = 16 * j * (D * 2);
 #pragma unroll
           for (int dt = 0; dt < DT; dt++) {
-            const bf16x8 at = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
+            const bf16x8 at = lds_tr_pair_at(tr_lo[dt] + rows, tr_hi[dt] + rows);
             acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at, as_bf16x8(b), acc[dt], 0, 0, 0);
           }
         }
       }
       td = nd; tq0 = nq0; have = nhave;
       nd = n2d; nq0 = n2q0; nhave = n2have;
-      t = (t == 2) ? 0 : t + 1;
+      next_buffer();
       pbuf ^= 1;
     }
 
@@ -720,25 +833,36 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
   constexpr int TB = tile_bytes<D>(kFwdTileN);
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_k[2][TB];
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_v[2][TB];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_kv[2][2 * TB];   // [buffer][K tile | V tile]
   __shared__ int s_item;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
   const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  const uint32_t dma_off = dma_lane_offset<D>(wave, lane, kv_row_stride);
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  int tr_lo[DT], tr_hi[DT], row_off[KC];
+  // absolute LDS addresses into the K tile of the CURRENT buffer (V = +TB), switched in place
+  uint32_t tr_lo[DT], tr_hi[DT], row_off[KC];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++) {
-    tr_lo[dt] = tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-    tr_hi[dt] = tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_lo[dt] = lds_addr(lds_kv[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = lds_addr(lds_kv[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
   }
 #pragma unroll
-  for (int kc = 0; kc < KC; kc++) row_off[kc] = tile_off<D>(l32, 2 * kc + g);
+  for (int kc = 0; kc < KC; kc++) row_off[kc] = lds_addr(lds_kv[0]) + tile_off<D>(l32, 2 * kc + g);
+  int buf = 0;                              // buffer the addresses above point into
+  auto switch_buffer = [&]() {
+    const int step = buf ? -2 * TB : 2 * TB;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += step; tr_hi[dt] += step; }
+#pragma unroll
+    for (int kc = 0; kc < KC; kc++) row_off[kc] += step;
+    buf ^= 1;
+  };
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->dq_counter, a.hdr->dq_begin);
@@ -782,26 +906,23 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
 
     TileIter ti;
     ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
-    auto dma = [&](int buf) {
+    auto dma = [&](int b) {
       const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
-      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
-      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane);
+      tile_dma<D, kFwdTileN, 4>(lds_kv[b], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      tile_dma<D, kFwdTileN, 4>(lds_kv[b] + TB, vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
     };
     DevPair tp = ti.cur;
     int tc0 = 0;
     bool have = ti.more;
-    if (have) { dma(0); ti.advance(); }
+    if (have) { dma(buf); ti.advance(); }
     dma_wait();
     __syncthreads();
-    int buf = 0;
     while (have) {
       const DevPair np = ti.cur;
       const int nc0 = ti.c0;
       const bool nhave = ti.more;
       if (nhave) { dma(buf ^ 1); ti.advance(); }
 
-      const unsigned char* tk = lds_k[buf];
-      const unsigned char* tv = lds_v[buf];
       const bool diag = tp.kind == FCP_KIND_DIAG;
       if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
         const bool need_mask = diag && tc0 + kFwdTileN - 1 > wave_row_lo;
@@ -814,26 +935,29 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
           for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
           for (int kc = 0; kc < KC; kc++) {
-            const u32x4 kk = *reinterpret_cast<const u32x4*>(tk + rt * 32 * (D * 2) + row_off[kc]);
-            const u32x4 vv = *reinterpret_cast<const u32x4*>(tv + rt * 32 * (D * 2) + row_off[kc]);
+            const u32x4 kk = lds_read16(row_off[kc] + rt * 32 * (D * 2));
+            const u32x4 vv = lds_read16(row_off[kc] + rt * 32 * (D * 2) + TB);
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kk), qf[kc], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vv), dof[kc], dp, 0, 0, 0);
           }
 #pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], a.scale_log2, -lse_l));
-            if (need_mask && tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) p = 0.f;
-            s[r] = p * __builtin_fmaf(dp[r], a.scale, -dl_l);
+          for (int r = 0; r < 16; r++) s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], a.scale_log2, -lse_l));
+          if (need_mask) {                    // wave-uniform: only tiles that straddle the diagonal
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+              if (tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) s[r] = 0.f;
           }
+#pragma unroll
+          for (int r = 0; r < 16; r++) s[r] *= __builtin_fmaf(dp[r], a.scale, -dl_l);
 #pragma unroll
           for (int j = 0; j < 2; j++) {
             u32x4 db;
 #pragma unroll
             for (int i = 0; i < 4; i++) db[i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
-            const unsigned char* base = tk + (rt * 32 + 16 * j) * (D * 2);
+            const uint32_t rows = (rt * 32 + 16 * j) * (D * 2);
 #pragma unroll
             for (int dt = 0; dt < DT; dt++) {
-              const bf16x8 kt = lds_tr_pair(base + tr_lo[dt], base + tr_hi[dt]);
+              const bf16x8 kt = lds_tr_pair_at(tr_lo[dt] + rows, tr_hi[dt] + rows);
               acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, as_bf16x8(db), acc[dt], 0, 0, 0);
             }
           }
@@ -842,7 +966,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
       tp = np; tc0 = nc0; have = nhave;
       dma_wait();
       __syncthreads();
-      buf ^= 1;
+      switch_buffer();
     }
     if (row_ok) {
       float* op = a.dq + (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D;
