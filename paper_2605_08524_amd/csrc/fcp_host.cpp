@@ -353,6 +353,12 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
       const fcp_block& qb = p->q_blocks[p->pairs[i].q_blk];
       deps[cursor[p->pairs[i].kv_blk]++] = {qb.tok_start, qb.tok_len, p->pairs[i].kind, 0};
     }
+    // The DIAG dependency goes last: the tiles of one KV block then walk the FULL dependencies in
+    // lockstep (identical step sequences, same XCD), so the Q / dO stream they share stays in L2;
+    // they only diverge on the diagonal block, where each tile starts at its own row.
+    for (int b = 0; b < p->n_kv_blocks; b++)
+      std::stable_partition(deps + dep_count[b], deps + dep_count[b + 1],
+                            [](const BwdDep& d) { return d.kind != FCP_KIND_DIAG; });
     std::vector<std::vector<BwdItem>> groups;
     std::vector<int64_t> weight;
     groups.reserve((size_t)p->n_kv_blocks * p->n_kv_heads);
