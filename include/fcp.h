@@ -164,21 +164,20 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
 
 /*
  * The three stages of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
- * fcp_bwd_preprocess:      writes D = rowsum(dO o O) ([T_q,Hq] fp32) into the workspace.
+ * fcp_bwd_preprocess:      computes D = rowsum(dO o O) and leaves scale*D and log2(e)*LSE
+ *                          ([Hq,T_q] fp32 each) in the workspace.
  * fcp_block_attn_bwd_dkdv: KV-stationary kernel, writes dk and dv.
  * fcp_block_attn_bwd_dq:   query-stationary kernel, writes dq.
  * The last two need fcp_bwd_preprocess to have run on the same workspace (same stream, or ordered
- * after it) with the same o / d_o, and are independent of each other.
+ * after it) with the same o / lse / d_o, and are independent of each other.
  * Arguments, layouts and errors as for fcp_block_attn_bwd.
  */
-int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o,
+int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const float* lse, const void* d_o,
                        void* workspace, void* stream);
 int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
-                            const float* lse, const void* d_o,
-                            float* dk, float* dv, void* workspace, void* stream);
+                            const void* d_o, float* dk, float* dv, void* workspace, void* stream);
 int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
-                          const float* lse, const void* d_o,
-                          float* dq, void* workspace, void* stream);
+                          const void* d_o, float* dq, void* workspace, void* stream);
 
 /* Text of the calling thread's last error ("" if none).  The pointer stays valid until the
  * thread's next failing call. */

@@ -61,9 +61,9 @@ def _load():
     lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
-    lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 4
-    lib.fcp_block_attn_bwd_dkdv.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 9
-    lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 8
+    lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
+    lib.fcp_block_attn_bwd_dkdv.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 8
+    lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
     for name in EXPORTS:
@@ -173,17 +173,17 @@ def fcp_block_attn_bwd(problem: Problem, q, k, v, o, lse, d_o, dq, dk, dv, works
                                    _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
 
 
-def fcp_bwd_preprocess(problem: Problem, o, d_o, workspace, stream=None):
-    _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(d_o), _ptr(workspace), _stream(stream)))
+def fcp_bwd_preprocess(problem: Problem, o, lse, d_o, workspace, stream=None):
+    _check(_lib.fcp_bwd_preprocess(problem.ref, _ptr(o), _ptr(lse), _ptr(d_o), _ptr(workspace), _stream(stream)))
 
 
-def fcp_block_attn_bwd_dkdv(problem: Problem, q, k, v, lse, d_o, dk, dv, workspace, stream=None):
-    _check(_lib.fcp_block_attn_bwd_dkdv(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
+def fcp_block_attn_bwd_dkdv(problem: Problem, q, k, v, d_o, dk, dv, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_dkdv(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(d_o),
                                         _ptr(dk), _ptr(dv), _ptr(workspace), _stream(stream)))
 
 
-def fcp_block_attn_bwd_dq(problem: Problem, q, k, v, lse, d_o, dq, workspace, stream=None):
-    _check(_lib.fcp_block_attn_bwd_dq(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(d_o),
+def fcp_block_attn_bwd_dq(problem: Problem, q, k, v, d_o, dq, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_dq(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(d_o),
                                       _ptr(dq), _ptr(workspace), _stream(stream)))
 
 

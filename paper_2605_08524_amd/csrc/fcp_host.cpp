@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -127,7 +128,9 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   L->off_merge_items = off; off = align(off + sizeof(MergeItem) * (size_t)std::max<int64_t>(1, L->n_merge_items));
   L->off_slot_rh = off;     off = align(off + sizeof(int32_t) * (size_t)std::max(1, p->n_slots));
   L->off_dq_items = off;    off = align(off + sizeof(FwdItem) * (size_t)std::max<int64_t>(1, L->n_dq_items));
-  L->off_delta = off;       off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
+  // backward scratch, head-major [Hq][T_q] fp32: D * scale, then LSE * log2(e)
+  L->off_dls = off;         off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
+  L->off_lse2 = off;        off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
   L->total = off;
   return FCP_OK;
 }
@@ -293,9 +296,10 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     set_error("fcp_queue_build: workspace too small (%zu < %zu)", workspace_bytes, L.total);
     return FCP_ERR_BUFFER_TOO_SMALL;
   }
-  const size_t upload = L.off_delta;   // everything before the D scratch region
+  const size_t upload = L.off_dls;   // everything before the backward scratch region
   std::vector<unsigned char> host(upload, 0);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(host.data());
+  for (float& x : hdr->infs) x = INFINITY;
   DevPair* dpairs = reinterpret_cast<DevPair*>(host.data() + L.off_pairs);
   for (int i = 0; i < p->n_pairs; i++) {
     const fcp_block& kb = p->kv_blocks[p->pairs[i].kv_blk];

@@ -35,13 +35,14 @@ struct WsHeader {
   int32_t dq_begin[kNumXcd + 1];
   int32_t pad3[7];
   int32_t zeros[64];                // 256-byte zero page: source of LDS-DMA loads past a ragged end
+  float infs[64];                   // +inf page: LSE of query rows past a ragged end (their P is 0)
 };
 
 // Byte offsets of the workspace sections, a pure function of the problem's counts.
 struct WsLayout {
   int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, n_dq_items, t_q, t_kv;
   int fwd_tile_m;   // query rows per forward item, chosen per problem
-  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_delta, total;
+  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_dls, off_lse2, total;
 };
 
 int validate_problem(const fcp_problem* p);           // host; sets the error text

@@ -120,6 +120,15 @@ __device__ __forceinline__ void lds_dma16_s(const unsigned char* sbase, uint32_t
                :: "v"(voff), "s"(sb), "s"(m0) : "memory", "m0");
 }
 #pragma clang diagnostic pop
+// Same for 64 x 4 bytes: lane i's dword lands at lds_addr + 4*i.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void lds_dma4(const float* gptr, uint32_t lds_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(gptr), "s"(m0) : "memory", "m0");
+}
+#pragma clang diagnostic pop
 // Byte offset, from the first row of a 1 KB load instruction, of the chunk that lane `lane` of
 // wave `wave` fetches.  Instruction n*NWAVES + wave covers rows that differ from wave's first
 // instruction by a multiple of 16, the period of the swizzle, so the offset is one per-lane
@@ -530,60 +539,100 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
 
 // =====================================================================================
 // Backward preprocess: D[t,h] = sum_c dO[t,h,c] * O[t,h,c].  HBM-bound.
+// Emits what the two backward kernels consume, head-major [Hq][T_q] so that 32 consecutive
+// query rows of one head are one 128-byte line:  dls = scale * D  and  lse2 = log2(e) * LSE,
+// with +inf in place of an LSE of -inf (a row that saw no key has P = 0 and no gradient).
+// One workgroup handles 16 tokens x all heads; results pass through LDS for the transposition.
 // =====================================================================================
+constexpr int kDeltaTok = 16;       // tokens per workgroup
+constexpr int kDeltaHeads = 128;    // heads per pass through LDS
+
 template <int D>
-__global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32, const uint16_t* d_o,
-                                                    float* delta, int64_t n_rh) {
-  constexpr int LPE = D / 8;      // lanes per entry, 8 elements each
-  const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPE;
-  const int ln = threadIdx.x % LPE;
-  float acc = 0.f;
-  if (e < n_rh) {
-    const u32x4 dv = *reinterpret_cast<const u32x4*>(d_o + e * D + ln * 8);
-    float ov[8];
-    if (o_is_f32) {
-      const f32x4 x0 = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(o) + e * D + ln * 8);
-      const f32x4 x1 = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(o) + e * D + ln * 8 + 4);
-      for (int i = 0; i < 4; i++) { ov[i] = x0[i]; ov[4 + i] = x1[i]; }
-    } else {
-      const u32x4 x = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(o) + e * D + ln * 8);
-      for (int i = 0; i < 4; i++) {
-        ov[2 * i] = __uint_as_float(x[i] << 16);
-        ov[2 * i + 1] = __uint_as_float(x[i] & 0xffff0000u);
+__global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32, const uint16_t* d_o, const float* lse,
+                                                    float* dls, float* lse2, int64_t t_q, int n_heads, float scale) {
+  constexpr int LPE = D / 8;      // lanes per (token, head) entry, 8 elements each
+  constexpr int EPP = 256 / LPE;  // entries per pass
+  __shared__ float sm_d[kDeltaHeads][kDeltaTok + 1];
+  __shared__ float sm_l[kDeltaHeads][kDeltaTok + 1];
+  const int64_t t0 = (int64_t)blockIdx.x * kDeltaTok;
+  const int n_tok = (int)min((int64_t)kDeltaTok, t_q - t0);
+  const int sub = threadIdx.x / LPE, ln = threadIdx.x % LPE;
+  for (int h0 = 0; h0 < n_heads; h0 += kDeltaHeads) {
+    const int nh = min(kDeltaHeads, n_heads - h0);
+    for (int e0 = 0; e0 < n_tok * nh; e0 += EPP) {
+      const int el = e0 + sub;                 // entry inside the (token, head chunk) tile
+      float acc = 0.f;
+      const bool ok = el < n_tok * nh;
+      const int tt = ok ? el / nh : 0, hh = ok ? el % nh : 0;
+      const int64_t e = (t0 + tt) * n_heads + h0 + hh;
+      if (ok) {
+        const u32x4 dv = *reinterpret_cast<const u32x4*>(d_o + e * D + ln * 8);
+        float ov[8];
+        if (o_is_f32) {
+          const f32x4 x0 = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(o) + e * D + ln * 8);
+          const f32x4 x1 = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(o) + e * D + ln * 8 + 4);
+          for (int i = 0; i < 4; i++) { ov[i] = x0[i]; ov[4 + i] = x1[i]; }
+        } else {
+          const u32x4 x = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(o) + e * D + ln * 8);
+          for (int i = 0; i < 4; i++) {
+            ov[2 * i] = __uint_as_float(x[i] << 16);
+            ov[2 * i + 1] = __uint_as_float(x[i] & 0xffff0000u);
+          }
+        }
+        for (int i = 0; i < 4; i++) {
+          acc += __uint_as_float(dv[i] << 16) * ov[2 * i];
+          acc += __uint_as_float(dv[i] & 0xffff0000u) * ov[2 * i + 1];
+        }
+      }
+      for (int off = LPE / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (ok && ln == 0) {
+        const float l = lse[e];
+        sm_d[hh][tt] = acc * scale;
+        sm_l[hh][tt] = (l == -INFINITY) ? INFINITY : l * kLog2e;
       }
     }
-    for (int i = 0; i < 4; i++) {
-      acc += __uint_as_float(dv[i] << 16) * ov[2 * i];
-      acc += __uint_as_float(dv[i] & 0xffff0000u) * ov[2 * i + 1];
+    __syncthreads();
+    for (int i = threadIdx.x; i < nh * kDeltaTok; i += 256) {
+      const int hh = i / kDeltaTok, tt = i % kDeltaTok;
+      if (tt < n_tok) {
+        const int64_t dst = (int64_t)(h0 + hh) * t_q + t0 + tt;
+        dls[dst] = sm_d[hh][tt];
+        lse2[dst] = sm_l[hh][tt];
+      }
     }
+    __syncthreads();
   }
-  for (int off = LPE / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (e < n_rh && ln == 0) delta[e] = acc;
 }
 
 // =====================================================================================
-// Backward, part 1 -- dK and dV.  Item = (KV tile of 128 rows, KV head); workgroup of 8 waves.
-// Wave w works on KV rows 32*(w%4) .. +32 of the tile in one of two roles, so that the two
-// waves sharing a SIMD split the four contractions evenly and neither holds more than one
-// accumulator set (no register spills at two waves per SIMD):
-//   role 0 (w < 4):  S = Q K^T -> P = exp2(S*c - LSE*log2e) -> hands P (fp32) to its partner
-//                    through LDS;  dV^T += dO^T P
-//   role 1 (w >= 4): dP = dO V^T;  dS = P o (dP - D) * scale;  dK^T += Q^T dS
-// S and dP take A from the Q / dO tiles in LDS (row-wise reads) and B from the wave's K or V
-// fragments in registers; dV^T and dK^T take A by transpose reads of the same tiles and B from
-// the accumulator registers.  Accumulators live in registers across every dependent query block
-// and the G query heads of the group; each dK / dV row has exactly one writer (plain stores).
-// Q / dO tiles of 32 rows are triple-buffered and filled by LDS-DMA two steps ahead: one
-// workgroup barrier per step (the one that publishes P).
+// Backward, part 1 -- dK and dV.  Item = (KV tile of 128 rows, KV head); workgroup of 8 waves, two
+// per SIMD.  KV rows 32*s .. +32 of the tile (s = wave % 4) are handled by a producer wave (s) and
+// a consumer wave (s + 4) that share a SIMD.  A step is 32 query rows of one head:
+//   producer  A(t): S = Q K^T, dP = dO V^T      (A operands: row-wise reads of the Q / dO tiles in
+//                                                LDS; B operands: the wave's K / V rows in registers)
+//             B(t): P = exp2(S*c - LSE*log2e), masked on the diagonal; dS = P o (dP*scale - D*scale);
+//                   P and dS go to the consumer as bf16 MFMA B operands through LDS
+//   consumer  C(t): dV^T += dO^T P, dK^T += Q^T dS   (A operands: transpose reads of the same tiles)
+// dK^T / dV^T (rows = d, cols = KV rows) stay in the consumer's accumulators across every dependent
+// query block and the G query heads of the group, so each dK / dV row has exactly one writer.
+// The roles are decoupled by whole steps: in one barrier interval the consumer runs C(t) while
+// the producer issues the MFMAs of A(t+2) with the vector work B(t+1) interleaved between them by
+// hand.  The vector ALU work of the SIMD thus sits in one wave and half of its MFMAs in the
+// other, and neither wave waits for the other inside an interval.  Q / dO tiles and the per-row
+// scalars sit in a ring of six LDS buffers filled by LDS-DMA (issued by the consumers) five steps
+// ahead of their C phase; one workgroup barrier per step.  Steps before the first and past the
+// last of an item run on +inf LSE (P = dS = 0), which keeps the instruction stream and the count
+// of loads in flight identical for every step; the ring runs on from item to item.
 // dQ is not produced here: accumulating it across KV tiles needs fp32 atomics, and the chip
 // sustains only about 1.35 TB/s of them (measured), several times below what this kernel would
 // emit.  dq_kernel below recomputes S and dP query-stationary instead.
 // =====================================================================================
 struct BwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
-  const float* lse; const float* delta;
+  const float* lse2; const float* dls;     // head-major [Hq][T_q]: LSE*log2(e) (+inf for empty rows), D*scale
   float* dq; float* dk; float* dv;
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const FwdItem* dq_items;
+  int64_t t_q;
   int32_t n_q_heads, n_kv_heads;
   float scale, scale_log2;
 };
@@ -617,49 +666,50 @@ struct StepIter {
   }
 };
 
+constexpr int kDkdvBufs = 6;        // ring of LDS step buffers
+constexpr int kNoMask = 1 << 30;    // diagonal threshold of a step that needs no mask
+
 template <int D>
-__global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
+__global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
+  constexpr int NS = 2 * KC;                 // MFMAs per wave and step (= 4 * DT)
+  constexpr int PF = 4;                      // an LDS operand is requested this many MFMAs before its use
   constexpr int TB = tile_bytes<D>(32);
-  // Each buffer holds [Q tile | dO tile].  Which of the two a wave reads depends on its role;
-  // that choice is folded into the per-lane offsets, so an LDS address is "buffer base + VGPR".
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_t[3][2 * TB];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_p[2][4][4096];   // [buffer][kv sub-tile][q4][lane] float4
-  __shared__ __attribute__((aligned(16))) float lds_lse[3][32];
-  __shared__ __attribute__((aligned(16))) float lds_dl[3][32];
+  constexpr int BUF = 2 * TB;                // [Q tile | dO tile]
+  constexpr int NB = kDkdvBufs;
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NDMA = 32 / RPI / 4;   // LDS-DMA geometry, see issue()
+  constexpr int DMA_PER_STEP = 2 * NDMA + 1;                        // instructions per consumer wave and step
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_t[NB][BUF];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_h[2][4][4096];   // [parity][KV sub-tile][operand][lane] 16 B
+  __shared__ __attribute__((aligned(256))) float lds_sc[NB][64];   // [LSE*log2e x 32 | D*scale x 32]
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
-  const int sub = wave & 3, role = wave >> 2;
+  const int sub = wave & 3;
+  const bool consumer = wave >= 4;
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
   const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
-  const uint32_t dma_off = dma_lane_offset<D>(sub, lane, q_row_stride);
-  const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  // absolute LDS addresses into the buffer of the CURRENT step, advanced in place every step
-  uint32_t tr_lo[DT], tr_hi[DT], row_off[KC];
-#pragma unroll
-  for (int dt = 0; dt < DT; dt++) {
-    // phase 2 reads the tile of the other role: dO^T for role 0, Q^T for role 1
-    tr_lo[dt] = lds_addr(lds_t[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
-    tr_hi[dt] = lds_addr(lds_t[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2 + (role ? 0 : TB);
-  }
-#pragma unroll
-  for (int kc = 0; kc < KC; kc++)   // phase 1: Q (role 0) or dO (role 1)
-    row_off[kc] = lds_addr(lds_t[0]) + tile_off<D>(l32, 2 * kc + g) + (role ? TB : 0);
-  int t = 0;            // step counter modulo 3: the tile buffer the addresses above point into
-  auto next_buffer = [&]() {
-    const int step = (t == 2) ? -4 * TB : 2 * TB;
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += step; tr_hi[dt] += step; }
-#pragma unroll
-    for (int kc = 0; kc < KC; kc++) row_off[kc] += step;
-    t = (t == 2) ? 0 : t + 1;
-  };
+  const float* infs = a.hdr->infs;
+  const uint32_t lds_sc0 = lds_addr(lds_sc[0]);
+  const uint32_t lds_h0 = lds_addr(lds_h[0][sub]) + lane * 16;
+
+  // Zero the tile ring and the hand-over buffers, +inf / 0 into the scalars: the steps before the
+  // first one of the first item then contribute nothing.
+  for (int i = tid * 16; i < NB * BUF; i += 512 * 16)
+    *reinterpret_cast<u32x4*>(&lds_t[0][0] + i) = u32x4{0, 0, 0, 0};
+  for (int i = tid * 16; i < 2 * 4 * 4096; i += 512 * 16)
+    *reinterpret_cast<u32x4*>(&lds_h[0][0][0] + i) = u32x4{0, 0, 0, 0};
+  for (int i = tid; i < NB * 64; i += 512) lds_sc[0][i] = (i & 32) ? 0.f : INFINITY;
+  // Ring positions, advanced by one buffer per step and kept across items.  In interval i the
+  // consumer transposes tile i (b_c), the producer reads the rows of tile i+2 and the scalars of
+  // step i+1, and the consumers request tile i+5 (b_dma).
+  int b_c = NB - 2, b_p = 0, b_s = NB - 1, b_dma = 3, hb = 0;
+  __syncthreads();
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->bwd_counter, a.hdr->bwd_begin);
@@ -669,150 +719,232 @@ __global__ void __launch_bounds__(512) dkdv_kernel(BwdArgs a) {
     const BwdItem it = a.items[item_idx];
     const int my_kv = sub * 32 + l32;                  // KV row inside the tile
     const bool kv_ok = my_kv < it.kv_rows;
-
-    // B operand of this wave's first contraction: K rows (role 0) or V rows (role 1);
-    // lane = KV row, 8 consecutive d per k-chunk.
-    bf16x8 bfr[KC];
-    {
-      const uint16_t* src = role ? a.v : a.k;
-      const int64_t off = (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D + 8 * g;
-#pragma unroll
-      for (int kc = 0; kc < KC; kc++) {
-        u32x4 z = {0, 0, 0, 0};
-        if (kv_ok) z = *reinterpret_cast<const u32x4*>(src + off + kc * 16);
-        bfr[kc] = as_bf16x8(z);
-      }
+    int n_iv = 2;       // barrier intervals of the item: its steps plus two of pipeline fill, rounded up to even
+    for (int d = 0; d < it.n_deps; d++) {
+      const BwdDep dd = a.deps[it.dep_begin + d];
+      const int first = dd.kind == FCP_KIND_DIAG ? (it.tile_off & ~31) : 0;
+      n_iv += group * ((dd.q_len - first + 31) / 32);
     }
-    f32x16 acc[DT];     // dV^T (role 0) or dK^T (role 1): rows = d, cols = this wave's KV rows
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
-
-    StepIter si;        // names the next step to LOAD
+    n_iv = (n_iv + 1) & ~1;
+    StepIter si;
     si.init(a.deps + it.dep_begin, it.n_deps, group, it.tile_off);
-    float p_lse = 0.f, p_dl = 0.f;
-    // Waves 0-3 fetch the Q tile, waves 4-7 the dO tile; the first 32 threads fetch LSE and D.
-    auto dma = [&](int buf) {
-      const int head = it.kv_head * group + si.hh;
-      const uint16_t* src = (role ? a.d_o : a.q) + (int64_t)(si.cur.q_start + si.q0) * q_row_stride + (int64_t)head * D;
-      tile_dma<D, 32, 4>(lds_t[buf] + (role ? TB : 0), src, q_row_stride, si.cur.q_len - si.q0, zeros, sub, lane, dma_off);
-      if (tid < 32) {
-        const int r = si.q0 + tid;
-        float l = INFINITY, dl = 0.f;      // rows past the end get P = exp2(-inf) = 0
-        if (r < si.cur.q_len) {
-          const int64_t rh = (int64_t)(si.cur.q_start + r) * a.n_q_heads + head;
-          l = a.lse[rh];
-          if (l == -INFINITY) l = INFINITY;  // a row that saw no key has no gradient
-          dl = a.delta[rh];
-        }
-        p_lse = l * kLog2e; p_dl = dl * a.scale;
-      }
-    };
-    auto publish_scalars = [&](int buf) { if (tid < 32) { lds_lse[buf][tid] = p_lse; lds_dl[buf][tid] = p_dl; } };
 
-    // prologue: steps 0 and 1 in LDS before the first barrier
-    BwdDep td = si.cur;
-    int tq0 = si.q0;
-    bool have = si.more;
-    BwdDep nd = td;
-    int nq0 = 0;
-    bool nhave = false;
-    if (have) {
-      const int t1 = (t == 2) ? 0 : t + 1;
-      dma(t); dma_wait(); publish_scalars(t);
-      si.advance();
-      nd = si.cur; nq0 = si.q0; nhave = si.more;
-      if (nhave) { dma(t1); dma_wait(); publish_scalars(t1); si.advance(); }
-    }
-    __syncthreads();
-    int pbuf = 0;       // parity of the P hand-over buffer
-    while (have) {
-      const bool diag = td.kind == FCP_KIND_DIAG;
-      const int kv_in_blk = it.tile_off + my_kv;
-      unsigned char* pslot = lds_p[pbuf][sub] + lane * 16;
-      f32x16 s;         // role 0: S then P;  role 1: dP then dS
+    if (consumer) {
+      // =============================== consumer ===============================
+      const int cw = sub;     // index among the four loading waves
+      // LDS-DMA of a 32-row tile: instruction n of this wave fills LDS rows r_n = (4n + cw) * RPI + lane / CPR.
+      // A lane fetches chunk (pc ^ swz(r_n)) of global row min(r_n, valid - 1): rows past a ragged end
+      // repeat the last valid row (finite values; their P is 0 because their LSE is +inf).
+      uint32_t dma_row[NDMA], dma_chunk[NDMA];
 #pragma unroll
-      for (int r = 0; r < 16; r++) s[r] = 0.f;
-      // ---- phase 1: S = Q K^T (role 0) or dP = dO V^T (role 1); rows = query, cols = KV
-      {
-#pragma unroll
-        for (int kc = 0; kc < KC; kc++) {
-          const u32x4 aa = lds_read16(row_off[kc]);
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aa), bfr[kc], s, 0, 0, 0);
-        }
+      for (int n = 0; n < NDMA; n++) {
+        const int r = (4 * n + cw) * RPI + lane / CPR, pc = lane % CPR;
+        dma_row[n] = (uint32_t)(r * q_row_stride * 2);
+        dma_chunk[n] = (uint32_t)((pc ^ swz<D>(r)) << 4);
       }
-      if (role == 0) {
-        // P (register r = query row 8*(r/4) + 4g + r%4, lane = KV row), handed to the partner wave
+      // scalars: lanes 0-31 fetch LSE*log2e of row lane, lanes 32-63 D*scale of row lane-32
+      const float* sc_arr = (g ? a.dls : a.lse2) + l32;
+      const float* sc_page = (g ? reinterpret_cast<const float*>(zeros) : infs) + l32;
+      const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      uint32_t tr_lo[DT], tr_hi[DT];       // transpose-read addresses inside a step buffer (Q tile; dO is +TB)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lds_lse[t][8 * q4 + 4 * g]);
-#pragma unroll
-          for (int i = 0; i < 4; i++)
-            s[4 * q4 + i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * q4 + i], a.scale_log2, -lse4[i]));
-        }
-        // only steps that straddle the diagonal need the mask (wave-uniform test)
-        if (diag && it.tile_off + sub * 32 + 31 > tq0) {
-#pragma unroll
-          for (int r = 0; r < 16; r++)
-            if (kv_in_blk > tq0 + 8 * (r >> 2) + 4 * g + (r & 3)) s[r] = 0.f;
-        }
-#pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 p4 = {s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(pslot + q4 * 1024) = p4;
-        }
+      for (int dt = 0; dt < DT; dt++) {
+        tr_lo[dt] = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+        tr_hi[dt] = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
       }
-      dma_wait();                 // this wave's share of step t+1's tiles has landed
-      publish_scalars(t == 2 ? 0 : t + 1);
-      __syncthreads();            // P(t) visible; step t+1 complete; everyone is past step t-1
-      // ---- step t+2 into the buffer that step t-1 used
-      const BwdDep n2d = si.cur;
-      const int n2q0 = si.q0;
-      const bool n2have = si.more;
-      if (n2have) { dma(t == 0 ? 2 : t - 1); si.advance(); }
-      // ---- phase 2
-      if (role == 1) {
-#pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          const f32x4 p4 = *reinterpret_cast<const f32x4*>(pslot + q4 * 1024);
-          const f32x4 dl4 = *reinterpret_cast<const f32x4*>(&lds_dl[t][8 * q4 + 4 * g]);
-#pragma unroll
-          for (int i = 0; i < 4; i++) s[4 * q4 + i] = p4[i] * __builtin_fmaf(s[4 * q4 + i], a.scale, -dl4[i]);
-        }
-      }
-      // dV^T += dO^T P (role 0) or dK^T += Q^T dS (role 1):
-      // k-slot (g, i) of chunk j = query 16j + 8(i/4) + 4g + i%4
-      {
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-          u32x4 b;
-#pragma unroll
-          for (int i = 0; i < 4; i++) b[i] = pack_bf16(s[8 * j + 2 * i], s[8 * j + 2 * i + 1]);
-          const uint32_t rows = 16 * j * (D * 2);
-#pragma unroll
-          for (int dt = 0; dt < DT; dt++) {
-            const bf16x8 at = lds_tr_pair_at(tr_lo[dt] + rows, tr_hi[dt] + rows);
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at, as_bf16x8(b), acc[dt], 0, 0, 0);
-          }
-        }
-      }
-      td = nd; tq0 = nq0; have = nhave;
-      nd = n2d; nq0 = n2q0; nhave = n2have;
-      next_buffer();
-      pbuf ^= 1;
-    }
-
-    // ---- epilogue: role 0 stores dV, role 1 stores dK (the only writer of these rows)
-    if (kv_ok) {
-      float* dst = (role ? a.dk : a.dv) + (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
+      f32x16 acc_k[DT], acc_v[DT];     // dK^T, dV^T: rows = d, cols = this pair's KV rows
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(dst + dt * 32 + 8 * q4 + 4 * g) = w;
+        for (int r = 0; r < 16; r++) { acc_k[dt][r] = 0.f; acc_v[dt][r] = 0.f; }
+
+      // The load of one step in two parts.  describe(): scalar bookkeeping with branches, run at a
+      // step boundary.  issue(): branch-free, sits between the MFMAs of the step.
+      uint64_t d_q = 0, d_do = 0;          // tile sources (row q0 of the head)
+      uint32_t d_lim = 0;                  // byte offset of the last valid row
+      int d_valid = 0;
+      int64_t d_sc = 0;                    // element offset of the step's first row in the head-major scalars
+      auto describe = [&]() {
+        d_q = reinterpret_cast<uint64_t>(zeros); d_do = d_q; d_lim = 0; d_valid = 0; d_sc = 0;
+        if (si.more) {
+          const int head = it.kv_head * group + si.hh;
+          const int64_t row = (int64_t)(si.cur.q_start + si.q0);
+          d_q = reinterpret_cast<uint64_t>(a.q + row * q_row_stride + (int64_t)head * D);
+          d_do = reinterpret_cast<uint64_t>(a.d_o + row * q_row_stride + (int64_t)head * D);
+          d_valid = min(32, si.cur.q_len - si.q0);
+          d_lim = (uint32_t)((d_valid - 1) * q_row_stride * 2);
+          d_sc = (int64_t)head * a.t_q + row;
+          si.advance();
         }
+      };
+      auto issue = [&]() {
+        const uint32_t lbase = lds_addr(lds_t[0]) + b_dma * BUF;
+#pragma unroll
+        for (int n = 0; n < NDMA; n++) {
+          const uint32_t voff = min(dma_row[n], d_lim) + dma_chunk[n];
+          lds_dma16_s(reinterpret_cast<const unsigned char*>(d_q), voff, lbase + (4 * n + cw) * 1024);
+          lds_dma16_s(reinterpret_cast<const unsigned char*>(d_do), voff, lbase + TB + (4 * n + cw) * 1024);
+        }
+        // all four loading waves fetch the 64 scalars (same values, same place): they then have
+        // the same number of loads in flight
+        const float* sp = (l32 < d_valid) ? sc_arr + d_sc : sc_page;
+        lds_dma4(sp, lds_sc0 + b_dma * 256);
+        b_dma = (b_dma == NB - 1) ? 0 : b_dma + 1;
+      };
+      // prologue: tiles 0 .. 2 into the three buffers before the next one to load
+      b_dma = (b_dma + NB - 3) % NB;
+#pragma unroll
+      for (int i = 0; i < 3; i++) { describe(); issue(); }
+      describe();          // tile 3, requested inside the first interval
+      dma_wait();
+      __syncthreads();
+
+      for (int iv = 0; iv < n_iv; iv++) {
+        // B operands of C(i): P (k-chunks 0, 1) and dS (k-chunks 0, 1) as left by the producer
+        u32x4 bop[4];
+#pragma unroll
+        for (int o = 0; o < 4; o++) bop[o] = lds_read16(lds_h0 + hb * (4 * 4096) + o * 1024);
+        u32x4 op[PF];
+        auto fetch = [&](int u) {
+          // operand u of C: j = k-chunk (16 query rows), w = 0: dO^T x P (dV), 1: Q^T x dS (dK)
+          const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
+          const uint32_t o = 16 * j * (D * 2) + (w == 0 ? TB : 0);
+          return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo[dt] + o, tr_hi[dt] + o));
+        };
+#pragma unroll
+        for (int u = 0; u < PF; u++) op[u] = fetch(u);
+#pragma unroll
+        for (int u = 0; u < NS; u++) {
+          const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
+          if (w == 0) acc_v[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), as_bf16x8(bop[j]), acc_v[dt], 0, 0, 0);
+          else acc_k[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), as_bf16x8(bop[2 + j]), acc_k[dt], 0, 0, 0);
+          if (u + PF < NS) op[u % PF] = fetch(u + PF);
+          if (u == NS / 2) issue();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // the tiles of step i+3 have landed once at most two steps' loads are in flight
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * DMA_PER_STEP) & 15) | (((2 * DMA_PER_STEP) >> 4) << 14));
+        __syncthreads();
+        describe();
+        {
+          const int st = (b_c == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+          for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += st; tr_hi[dt] += st; }
+          b_c = (b_c == NB - 1) ? 0 : b_c + 1;
+          hb ^= 1;
+        }
+      }
+      dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
+
+      // ---- epilogue: the only writer of these dK / dV rows
+      if (kv_ok) {
+        const int64_t off = (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            f32x4 wk = {acc_k[dt][4 * q4], acc_k[dt][4 * q4 + 1], acc_k[dt][4 * q4 + 2], acc_k[dt][4 * q4 + 3]};
+            f32x4 wv = {acc_v[dt][4 * q4], acc_v[dt][4 * q4 + 1], acc_v[dt][4 * q4 + 2], acc_v[dt][4 * q4 + 3]};
+            *reinterpret_cast<f32x4*>(a.dk + off + dt * 32 + 8 * q4 + 4 * g) = wk;
+            *reinterpret_cast<f32x4*>(a.dv + off + dt * 32 + 8 * q4 + 4 * g) = wv;
+          }
+      }
+    } else {
+      // =============================== producer ===============================
+      const int kvg = it.tile_off + my_kv - 4 * g;       // masked iff kvg > q0 + 8*(r/4) + r%4 on a DIAG step
+      // B operands of S and dP: this pair's K and V rows; lane = KV row, 8 consecutive d per k-chunk.
+      bf16x8 kf[KC], vf[KC];
+      {
+        const int64_t off = (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D + 8 * g;
+#pragma unroll
+        for (int kc = 0; kc < KC; kc++) {
+          u32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
+          if (kv_ok) {
+            zk = *reinterpret_cast<const u32x4*>(a.k + off + kc * 16);
+            zv = *reinterpret_cast<const u32x4*>(a.v + off + kc * 16);
+          }
+          kf[kc] = as_bf16x8(zk); vf[kc] = as_bf16x8(zv);
+        }
+      }
+      uint32_t row_a[KC];        // row-read addresses inside the step buffer of tile i+2 (Q tile; dO is +TB)
+#pragma unroll
+      for (int kc = 0; kc < KC; kc++) row_a[kc] = lds_addr(lds_t[0]) + b_p * BUF + tile_off<D>(l32, 2 * kc + g);
+      // diagonal thresholds of the steps i+1, i+2, ... as the iterator reaches them: B(i+1) runs in
+      // interval i, and the item's step 0 has i+1 = 0 in interval -1 (the second one)
+      int thr_next = kNoMask;    // threshold of the step that B handles in the NEXT interval
+      f32x16 s_a, dp_a, s_b, dp_b;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { s_a[r] = 0.f; dp_a[r] = 0.f; s_b[r] = 0.f; dp_b[r] = 0.f; }
+      dma_wait();          // K / V fragments
+      __syncthreads();     // the prologue's tiles are in place
+
+      // One interval: MFMAs of A(i+2) into (sn, dpn); B(i+1) on (sc, dpc) between them.
+      auto interval = [&](f32x16& sc, f32x16& dpc, f32x16& sn, f32x16& dpn) {
+        const int thr_t = __builtin_amdgcn_readfirstlane(thr_next);
+        // scalars of step i+1
+        f32x4 lse4[4], dl4[4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          lse4[q4] = __builtin_bit_cast(f32x4, lds_read16(lds_sc0 + b_s * 256 + 16 * g + 32 * q4));
+          dl4[q4] = __builtin_bit_cast(f32x4, lds_read16(lds_sc0 + b_s * 256 + 16 * g + 32 * q4 + 128));
+        }
+        u32x4 op[PF];
+#pragma unroll
+        for (int k = 0; k < PF; k++) op[k] = lds_read16(row_a[k / 2] + ((k & 1) ? TB : 0));
+        uint32_t pk[16];           // [0..7] P pairs, [8..15] dS pairs: four B operands for the consumer
+        float p_prev = 0.f, ds_prev = 0.f;
+        const uint32_t hdst = lds_h0 + (hb ^ 1) * (4 * 4096);
+#pragma unroll
+        for (int k = 0; k < NS; k++) {
+          const int kc = k / 2;
+          if (k == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) { sn[r] = 0.f; dpn[r] = 0.f; }
+          }
+          if ((k & 1) == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PF]), kf[kc], sn, 0, 0, 0);
+          else dpn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PF]), vf[kc], dpn, 0, 0, 0);
+          if (k + PF < NS) op[k % PF] = lds_read16(row_a[(k + PF) / 2] + (((k + PF) & 1) ? TB : 0));
+          // vector work: 16 / NS score registers per slot
+#pragma unroll
+          for (int r = k * 16 / NS; r < (k + 1) * 16 / NS; r++) {
+            const float lse_r = lse4[r >> 2][r & 3], dl_r = dl4[r >> 2][r & 3];
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], a.scale_log2, -lse_r));
+            p = (kvg > thr_t + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
+            const float ds = p * __builtin_fmaf(dpc[r], a.scale, -dl_r);
+            if (r & 1) {
+              pk[r >> 1] = pack_bf16(p_prev, p); pk[8 + (r >> 1)] = pack_bf16(ds_prev, ds);
+              // keeps the vector work between the MFMAs it was written between
+              asm volatile("" :: "v"(pk[r >> 1]), "v"(pk[8 + (r >> 1)]));
+            } else { p_prev = p; ds_prev = ds; }
+            if ((r & 7) == 7) {
+              // rows 8*(r/8) .. r done: one P operand and one dS operand (k-chunk r/8)
+              const int j = r >> 3;
+              const u32x4 wp = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+              const u32x4 wd = {pk[8 + 4 * j], pk[8 + 4 * j + 1], pk[8 + 4 * j + 2], pk[8 + 4 * j + 3]};
+              *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(hdst + j * 1024) = wp;
+              *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(hdst + (2 + j) * 1024) = wd;
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        // the step that B handles next
+        thr_next = kNoMask;
+        if (si.more) { if (si.cur.kind == FCP_KIND_DIAG) thr_next = si.q0; si.advance(); }
+        {
+          const int st = (b_p == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+          for (int kc = 0; kc < KC; kc++) row_a[kc] += st;
+          b_p = (b_p == NB - 1) ? 0 : b_p + 1;
+          b_s = (b_s == NB - 1) ? 0 : b_s + 1;
+          hb ^= 1;
+        }
+      };
+      // the first interval handles B(-1) (nothing) and A(0), the second B(0) and A(1), ...
+      for (int iv = 0; iv < n_iv; iv += 2) {
+        interval(s_a, dp_a, s_b, dp_b);
+        interval(s_b, dp_b, s_a, dp_a);
+      }
     }
     __syncthreads();
   }
@@ -891,11 +1023,9 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
         qf[kc] = as_bf16x8(zq); dof[kc] = as_bf16x8(zd);
       }
       if (row_ok) {
-        const int64_t rh = (int64_t)(it.q_start + my_row) * a.n_q_heads + it.head;
-        float l = a.lse[rh];
-        if (l == -INFINITY) l = INFINITY;
-        lse_l = l * kLog2e;
-        dl_l = a.delta[rh] * a.scale;
+        const int64_t hr = (int64_t)it.head * a.t_q + it.q_start + my_row;
+        lse_l = a.lse2[hr];
+        dl_l = a.dls[hr];
       }
     }
     f32x16 acc[DT];
@@ -1009,7 +1139,7 @@ static float resolve_scale(const fcp_problem* p) {
 }
 
 constexpr int kFwdWgPerCu = 2;
-constexpr int kDkdvWgPerCu = 1;   // 8 waves each
+constexpr int kDkdvWgPerCu = 1;   // 8 waves, two per SIMD
 constexpr int kDqWgPerCu = 2;
 
 }  // namespace fcp
@@ -1068,23 +1198,24 @@ extern "C" int fcp_merge_partials(const fcp_problem* p, const float* o_part, con
   return check_launch("fcp_merge_partials");
 }
 
-extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const void* d_o,
+extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const float* lse, const void* d_o,
                                   void* workspace, void* stream) {
   int rc = validate_problem(p);
   if (rc) return rc;
   WsLayout L;
   rc = compute_layout(p, &L);
   if (rc) return rc;
-  const int64_t n_rh = L.t_q * p->n_q_heads;
-  if (n_rh == 0) return FCP_OK;
-  if (!o || !d_o || !workspace) { set_error("fcp_bwd_preprocess: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (L.t_q == 0) return FCP_OK;
+  if (!o || !lse || !d_o || !workspace) { set_error("fcp_bwd_preprocess: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   hipStream_t st = (hipStream_t)stream;
-  float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + L.off_delta);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  float* dls = reinterpret_cast<float*>(ws + L.off_dls);
+  float* lse2 = reinterpret_cast<float*>(ws + L.off_lse2);
   const int o_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
-  const int D = p->head_dim;
-  const int64_t blocks = (n_rh * (D / 8) + 255) / 256;
-  if (D == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, delta, n_rh);
-  else hipLaunchKernelGGL(delta_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, delta, n_rh);
+  const float scale = resolve_scale(p);
+  const unsigned blocks = (unsigned)((L.t_q + kDeltaTok - 1) / kDeltaTok);
+  if (p->head_dim == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3(blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, lse, dls, lse2, L.t_q, p->n_q_heads, scale);
+  else hipLaunchKernelGGL(delta_kernel<64>, dim3(blocks), dim3(256), 0, st, o, o_f32, (const uint16_t*)d_o, lse, dls, lse2, L.t_q, p->n_q_heads, scale);
   return check_launch("fcp_bwd_preprocess");
 }
 
@@ -1095,7 +1226,9 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
   if (rc) return rc;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   a->hdr = reinterpret_cast<WsHeader*>(ws);
-  a->delta = reinterpret_cast<const float*>(ws + L->off_delta);
+  a->dls = reinterpret_cast<const float*>(ws + L->off_dls);
+  a->lse2 = reinterpret_cast<const float*>(ws + L->off_lse2);
+  a->t_q = L->t_q;
   a->pairs = reinterpret_cast<const DevPair*>(ws + L->off_pairs);
   a->deps = reinterpret_cast<const BwdDep*>(ws + L->off_bwd_deps);
   a->items = reinterpret_cast<const BwdItem*>(ws + L->off_bwd_items);
@@ -1107,16 +1240,15 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
 }
 
 extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                       const float* lse, const void* d_o,
-                                       float* dk, float* dv, void* workspace, void* stream) {
+                                       const void* d_o, float* dk, float* dv, void* workspace, void* stream) {
   WsLayout L;
   BwdArgs a;
   int rc = fill_bwd_args(p, &L, &a, workspace);
   if (rc) return rc;
   if (L.n_bwd_items == 0) return FCP_OK;
-  if (!q || !k || !v || !lse || !d_o || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_dkdv: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !d_o || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_dkdv: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
-  a.lse = lse; a.dk = dk; a.dv = dv;
+  a.dk = dk; a.dv = dv;
   const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
   if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
@@ -1124,16 +1256,15 @@ extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, cons
 }
 
 extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                     const float* lse, const void* d_o,
-                                     float* dq, void* workspace, void* stream) {
+                                     const void* d_o, float* dq, void* workspace, void* stream) {
   WsLayout L;
   BwdArgs a;
   int rc = fill_bwd_args(p, &L, &a, workspace);
   if (rc) return rc;
   if (L.n_dq_items == 0) return FCP_OK;
-  if (!q || !k || !v || !lse || !d_o || !dq || !workspace) { set_error("fcp_block_attn_bwd_dq: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !d_o || !dq || !workspace) { set_error("fcp_block_attn_bwd_dq: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
-  a.lse = lse; a.dq = dq;
+  a.dq = dq;
   const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
   if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
@@ -1149,9 +1280,9 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
     set_error("fcp_block_attn_bwd: NULL pointer");
     return FCP_ERR_INVALID_ARG;
   }
-  int rc = fcp_bwd_preprocess(p, o, d_o, workspace, stream);
+  int rc = fcp_bwd_preprocess(p, o, lse, d_o, workspace, stream);
   if (rc) return rc;
-  rc = fcp_block_attn_bwd_dkdv(p, q, k, v, lse, d_o, dk, dv, workspace, stream);
+  rc = fcp_block_attn_bwd_dkdv(p, q, k, v, d_o, dk, dv, workspace, stream);
   if (rc) return rc;
-  return fcp_block_attn_bwd_dq(p, q, k, v, lse, d_o, dq, workspace, stream);
+  return fcp_block_attn_bwd_dq(p, q, k, v, d_o, dq, workspace, stream);
 }

@@ -57,14 +57,14 @@ class DevicePath:
 
 
     def bwd_pre(self):
-        B.fcp_bwd_preprocess(self.problem, self.o, self.d_o, self.ws_ptr, self.stream)
+        B.fcp_bwd_preprocess(self.problem, self.o, self.lse, self.d_o, self.ws_ptr, self.stream)
 
     def bwd_dkdv(self):
-        B.fcp_block_attn_bwd_dkdv(self.problem, self.q, self.k, self.v, self.lse, self.d_o,
+        B.fcp_block_attn_bwd_dkdv(self.problem, self.q, self.k, self.v, self.d_o,
                                   self.dk, self.dv, self.ws_ptr, self.stream)
 
     def bwd_dq(self):
-        B.fcp_block_attn_bwd_dq(self.problem, self.q, self.k, self.v, self.lse, self.d_o,
+        B.fcp_block_attn_bwd_dq(self.problem, self.q, self.k, self.v, self.d_o,
                                 self.dq, self.ws_ptr, self.stream)
 
 
