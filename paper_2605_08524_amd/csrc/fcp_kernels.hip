@@ -18,6 +18,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "fcp_internal.h"
 
@@ -619,10 +620,16 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32,
 // the producer issues the MFMAs of A(t+2) with the vector work B(t+1) interleaved between them by
 // hand.  The vector ALU work of the SIMD thus sits in one wave and half of its MFMAs in the
 // other, and neither wave waits for the other inside an interval.  Q / dO tiles and the per-row
-// scalars sit in a ring of six LDS buffers filled by LDS-DMA (issued by the consumers) five steps
-// ahead of their C phase; one workgroup barrier per step.  Steps before the first and past the
-// last of an item run on +inf LSE (P = dS = 0), which keeps the instruction stream and the count
-// of loads in flight identical for every step; the ring runs on from item to item.
+// scalars sit in a ring of seven LDS buffers filled by LDS-DMA (issued by the consumers) six
+// steps ahead of their C phase; a tile is in place two intervals before the producer reads it,
+// so both roles request the first LDS operands of an interval before the barrier that opens it.
+// One workgroup barrier per step.  Steps before the first and past the last of an item run on
+// +inf LSE (P = dS = 0), which keeps the instruction stream and the count of loads in flight
+// identical for every step; the ring runs on from item to item.
+// The kernel is bound by LDS time, not by the matrix pipe: per step and SIMD pair the LDS serves
+// 16 row reads + 8 scalar reads (b128, 256 B/clk), 32 transpose reads (b64, 160 B/clk), the
+// 8 KB hand-over and the 4 KB of DMA writes (writes: 76 B/clk), about 1.25x the 1024 cycles of
+// the 32 MFMAs (rates measured on this chip).
 // dQ is not produced here: accumulating it across KV tiles needs fp32 atomics, and the chip
 // sustains only about 1.35 TB/s of them (measured), several times below what this kernel would
 // emit.  dq_kernel below recomputes S and dP query-stationary instead.
@@ -666,7 +673,7 @@ struct StepIter {
   }
 };
 
-constexpr int kDkdvBufs = 6;        // ring of LDS step buffers
+constexpr int kDkdvBufs = 7;        // ring of LDS step buffers
 constexpr int kNoMask = 1 << 30;    // diagonal threshold of a step that needs no mask
 
 template <int D>
@@ -674,7 +681,8 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
   constexpr int NS = 2 * KC;                 // MFMAs per wave and step (= 4 * DT)
-  constexpr int PF = 4;                      // an LDS operand is requested this many MFMAs before its use
+  constexpr int PFC = 4;                     // consumer: an LDS operand is requested this many MFMAs before its use
+  constexpr int PFP = 4;                     // producer
   constexpr int TB = tile_bytes<D>(32);
   constexpr int BUF = 2 * TB;                // [Q tile | dO tile]
   constexpr int NB = kDkdvBufs;
@@ -707,8 +715,10 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   for (int i = tid; i < NB * 64; i += 512) lds_sc[0][i] = (i & 32) ? 0.f : INFINITY;
   // Ring positions, advanced by one buffer per step and kept across items.  In interval i the
   // consumer transposes tile i (b_c), the producer reads the rows of tile i+2 and the scalars of
-  // step i+1, and the consumers request tile i+5 (b_dma).
-  int b_c = NB - 2, b_p = 0, b_s = NB - 1, b_dma = 3, hb = 0;
+  // step i+1 (b_p, b_s), and the consumers request tile i+6 (b_dma).  A tile is in place (landed
+  // and published by a barrier) two intervals before the producer's interval, so both roles can
+  // request their first LDS operands of an interval before the barrier that opens it.
+  int b_c = NB - 2, b_p = 0, b_s = NB - 1, b_dma = 4, hb = 0;
   __syncthreads();
 
   for (;;) {
@@ -791,48 +801,49 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         lds_dma4(sp, lds_sc0 + b_dma * 256);
         b_dma = (b_dma == NB - 1) ? 0 : b_dma + 1;
       };
-      // prologue: tiles 0 .. 2 into the three buffers before the next one to load
-      b_dma = (b_dma + NB - 3) % NB;
+      // prologue: tiles 0 .. 3 into the four buffers before the next one to load
+      b_dma = (b_dma + NB - 4) % NB;
 #pragma unroll
-      for (int i = 0; i < 3; i++) { describe(); issue(); }
-      describe();          // tile 3, requested inside the first interval
+      for (int i = 0; i < 4; i++) { describe(); issue(); }
+      describe();          // tile 4, requested inside the first interval
       dma_wait();
       __syncthreads();
+      u32x4 op[PFC];        // transposed operands, requested PFC MFMAs ahead (across the barrier too)
+      auto fetch = [&](int u) {
+        // operand u of C: j = k-chunk (16 query rows), w = 0: dO^T x P (dV), 1: Q^T x dS (dK)
+        const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
+        const uint32_t o = 16 * j * (D * 2) + (w == 0 ? TB : 0);
+        return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo[dt] + o, tr_hi[dt] + o));
+      };
+#pragma unroll
+      for (int u = 0; u < PFC; u++) op[u] = fetch(u);
 
       for (int iv = 0; iv < n_iv; iv++) {
         // B operands of C(i): P (k-chunks 0, 1) and dS (k-chunks 0, 1) as left by the producer
         u32x4 bop[4];
 #pragma unroll
         for (int o = 0; o < 4; o++) bop[o] = lds_read16(lds_h0 + hb * (4 * 4096) + o * 1024);
-        u32x4 op[PF];
-        auto fetch = [&](int u) {
-          // operand u of C: j = k-chunk (16 query rows), w = 0: dO^T x P (dV), 1: Q^T x dS (dK)
-          const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
-          const uint32_t o = 16 * j * (D * 2) + (w == 0 ? TB : 0);
-          return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo[dt] + o, tr_hi[dt] + o));
-        };
-#pragma unroll
-        for (int u = 0; u < PF; u++) op[u] = fetch(u);
 #pragma unroll
         for (int u = 0; u < NS; u++) {
           const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
-          if (w == 0) acc_v[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), as_bf16x8(bop[j]), acc_v[dt], 0, 0, 0);
-          else acc_k[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), as_bf16x8(bop[2 + j]), acc_k[dt], 0, 0, 0);
-          if (u + PF < NS) op[u % PF] = fetch(u + PF);
+          if (w == 0) acc_v[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PFC]), as_bf16x8(bop[j]), acc_v[dt], 0, 0, 0);
+          else acc_k[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PFC]), as_bf16x8(bop[2 + j]), acc_k[dt], 0, 0, 0);
+          if (u == NS - PFC) {
+            // the last operand of this tile has been requested: move on to the next tile
+            const int st = (b_c == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+            for (int dt2 = 0; dt2 < DT; dt2++) { tr_lo[dt2] += st; tr_hi[dt2] += st; }
+            b_c = (b_c == NB - 1) ? 0 : b_c + 1;
+          }
+          op[u % PFC] = fetch((u + PFC) % NS);
           if (u == NS / 2) issue();
           __builtin_amdgcn_sched_barrier(0);
         }
-        // the tiles of step i+3 have landed once at most two steps' loads are in flight
+        // the tiles of step i+4 have landed once at most two steps' loads are in flight
         __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * DMA_PER_STEP) & 15) | (((2 * DMA_PER_STEP) >> 4) << 14));
         __syncthreads();
         describe();
-        {
-          const int st = (b_c == NB - 1) ? -(NB - 1) * BUF : BUF;
-#pragma unroll
-          for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += st; tr_hi[dt] += st; }
-          b_c = (b_c == NB - 1) ? 0 : b_c + 1;
-          hb ^= 1;
-        }
+        hb ^= 1;
       }
       dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
 
@@ -869,28 +880,24 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       uint32_t row_a[KC];        // row-read addresses inside the step buffer of tile i+2 (Q tile; dO is +TB)
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) row_a[kc] = lds_addr(lds_t[0]) + b_p * BUF + tile_off<D>(l32, 2 * kc + g);
-      // diagonal thresholds of the steps i+1, i+2, ... as the iterator reaches them: B(i+1) runs in
-      // interval i, and the item's step 0 has i+1 = 0 in interval -1 (the second one)
-      int thr_next = kNoMask;    // threshold of the step that B handles in the NEXT interval
+      uint32_t sc_a = lds_sc0 + b_s * 256 + 16 * g;      // scalars of step i+1: rows 8*q4 + 4g .. +3 at +32*q4, D*scale at +128
+      int thr_t = kNoMask;       // diagonal threshold of the step that B handles in this interval
       f32x16 s_a, dp_a, s_b, dp_b;
 #pragma unroll
       for (int r = 0; r < 16; r++) { s_a[r] = 0.f; dp_a[r] = 0.f; s_b[r] = 0.f; dp_b[r] = 0.f; }
       dma_wait();          // K / V fragments
       __syncthreads();     // the prologue's tiles are in place
+      // requested before an interval starts: its first PFP row operands and its first four scalars
+      u32x4 op[PFP];
+#pragma unroll
+      for (int k = 0; k < PFP; k++) op[k] = lds_read16(row_a[k / 2] + ((k & 1) ? TB : 0));
+      f32x4 lse_n = __builtin_bit_cast(f32x4, lds_read16(sc_a)), dl_n = __builtin_bit_cast(f32x4, lds_read16(sc_a + 128));
 
       // One interval: MFMAs of A(i+2) into (sn, dpn); B(i+1) on (sc, dpc) between them.
-      auto interval = [&](f32x16& sc, f32x16& dpc, f32x16& sn, f32x16& dpn) {
-        const int thr_t = __builtin_amdgcn_readfirstlane(thr_next);
-        // scalars of step i+1
-        f32x4 lse4[4], dl4[4];
-#pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          lse4[q4] = __builtin_bit_cast(f32x4, lds_read16(lds_sc0 + b_s * 256 + 16 * g + 32 * q4));
-          dl4[q4] = __builtin_bit_cast(f32x4, lds_read16(lds_sc0 + b_s * 256 + 16 * g + 32 * q4 + 128));
-        }
-        u32x4 op[PF];
-#pragma unroll
-        for (int k = 0; k < PF; k++) op[k] = lds_read16(row_a[k / 2] + ((k & 1) ? TB : 0));
+      auto interval = [&](auto masked, f32x16& sc, f32x16& dpc, f32x16& sn, f32x16& dpn) {
+        constexpr bool MASK = decltype(masked)::value;
+        const int thr_s = __builtin_amdgcn_readfirstlane(thr_t);
+        f32x4 lse_c = lse_n, dl_c = dl_n;      // scalars of rows 8*q4 + 4g .. +3, one group of four ahead
         uint32_t pk[16];           // [0..7] P pairs, [8..15] dS pairs: four B operands for the consumer
         float p_prev = 0.f, ds_prev = 0.f;
         const uint32_t hdst = lds_h0 + (hb ^ 1) * (4 * 4096);
@@ -901,15 +908,38 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; r++) { sn[r] = 0.f; dpn[r] = 0.f; }
           }
-          if ((k & 1) == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PF]), kf[kc], sn, 0, 0, 0);
-          else dpn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PF]), vf[kc], dpn, 0, 0, 0);
-          if (k + PF < NS) op[k % PF] = lds_read16(row_a[(k + PF) / 2] + (((k + PF) & 1) ? TB : 0));
+          if ((k & 1) == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PFP]), kf[kc], sn, 0, 0, 0);
+          else dpn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[k % PFP]), vf[kc], dpn, 0, 0, 0);
+          if (k == NS - PFP) {
+            // the last row operand of this tile has been requested: move on to the next tile
+            const int st = (b_p == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+            for (int kc2 = 0; kc2 < KC; kc2++) row_a[kc2] += st;
+            b_p = (b_p == NB - 1) ? 0 : b_p + 1;
+          }
+          {
+            const int kk = (k + PFP) % NS;
+            op[k % PFP] = lds_read16(row_a[kk / 2] + ((kk & 1) ? TB : 0));
+          }
           // vector work: 16 / NS score registers per slot
 #pragma unroll
           for (int r = k * 16 / NS; r < (k + 1) * 16 / NS; r++) {
-            const float lse_r = lse4[r >> 2][r & 3], dl_r = dl4[r >> 2][r & 3];
+            if ((r & 3) == 0) {
+              if (r > 0) { lse_c = lse_n; dl_c = dl_n; }
+              if (r == 12) {
+                // the scalars of the next interval's first four rows
+                sc_a += (b_s == NB - 1) ? -(NB - 1) * 256 : 256;
+                b_s = (b_s == NB - 1) ? 0 : b_s + 1;
+                lse_n = __builtin_bit_cast(f32x4, lds_read16(sc_a));
+                dl_n = __builtin_bit_cast(f32x4, lds_read16(sc_a + 128));
+              } else {
+                lse_n = __builtin_bit_cast(f32x4, lds_read16(sc_a + 32 * ((r >> 2) + 1)));
+                dl_n = __builtin_bit_cast(f32x4, lds_read16(sc_a + 32 * ((r >> 2) + 1) + 128));
+              }
+            }
+            const float lse_r = lse_c[r & 3], dl_r = dl_c[r & 3];
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], a.scale_log2, -lse_r));
-            p = (kvg > thr_t + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
+            if constexpr (MASK) p = (kvg > thr_s + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
             const float ds = p * __builtin_fmaf(dpc[r], a.scale, -dl_r);
             if (r & 1) {
               pk[r >> 1] = pack_bf16(p_prev, p); pk[8 + (r >> 1)] = pack_bf16(ds_prev, ds);
@@ -929,21 +959,16 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         }
         __syncthreads();
         // the step that B handles next
-        thr_next = kNoMask;
-        if (si.more) { if (si.cur.kind == FCP_KIND_DIAG) thr_next = si.q0; si.advance(); }
-        {
-          const int st = (b_p == NB - 1) ? -(NB - 1) * BUF : BUF;
-#pragma unroll
-          for (int kc = 0; kc < KC; kc++) row_a[kc] += st;
-          b_p = (b_p == NB - 1) ? 0 : b_p + 1;
-          b_s = (b_s == NB - 1) ? 0 : b_s + 1;
-          hb ^= 1;
-        }
+        thr_t = kNoMask;
+        if (si.more) { if (si.cur.kind == FCP_KIND_DIAG) thr_t = si.q0; si.advance(); }
+        hb ^= 1;
       };
       // the first interval handles B(-1) (nothing) and A(0), the second B(0) and A(1), ...
+      const std::true_type with_mask;
+      const std::false_type no_mask;
       for (int iv = 0; iv < n_iv; iv += 2) {
-        interval(s_a, dp_a, s_b, dp_b);
-        interval(s_b, dp_b, s_a, dp_a);
+        if (thr_t != kNoMask) interval(with_mask, s_a, dp_a, s_b, dp_b); else interval(no_mask, s_a, dp_a, s_b, dp_b);
+        if (thr_t != kNoMask) interval(with_mask, s_b, dp_b, s_a, dp_a); else interval(no_mask, s_b, dp_b, s_a, dp_a);
       }
     }
     __syncthreads();
@@ -1249,7 +1274,7 @@ extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, cons
   if (!q || !k || !v || !d_o || !dk || !dv || !workspace) { set_error("fcp_block_attn_bwd_dkdv: NULL pointer"); return FCP_ERR_INVALID_ARG; }
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dk = dk; a.dv = dv;
-  const int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
+  int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
   if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch("fcp_block_attn_bwd_dkdv");
