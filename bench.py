@@ -23,9 +23,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# scaled by a copy kernel of known size (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a
+# plain copy of known size in the same runs (profiles/cfg5_training_step_hbm_traffic.txt); None
+# for a workload or kernel that has not been measured.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.799e9,
+    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 7.103e9,
+    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 3.374e9,
+}
 
 
 def pair_flops(plan, n_q_heads, head_dim):
