@@ -104,8 +104,14 @@ int validate_problem(const fcp_problem* p) {
 int compute_layout(const fcp_problem* p, WsLayout* L) {
   std::memset(L, 0, sizeof(*L));
   L->fwd_tile_m = kFwdTileM;
-  for (int s = 0; s < p->n_slots; s++)
-    L->n_fwd_items += ceil_div(p->q_blocks[p->slots[s].q_blk].tok_len, L->fwd_tile_m) * p->n_q_heads;
+  {
+    // forward items pair two query heads of a KV head when the group size is even, else two row tiles
+    const int G = p->n_q_heads / p->n_kv_heads;
+    for (int s = 0; s < p->n_slots; s++) {
+      const int64_t n_tiles = ceil_div(p->q_blocks[p->slots[s].q_blk].tok_len, L->fwd_tile_m);
+      L->n_fwd_items += (G % 2 == 0) ? n_tiles * (p->n_q_heads / 2) : ceil_div(n_tiles, 2) * p->n_q_heads;
+    }
+  }
   for (int b = 0; b < p->n_kv_blocks; b++)
     L->n_bwd_items += ceil_div(p->kv_blocks[b].tok_len, kBwdTileN) * p->n_kv_heads;
   L->n_bwd_deps = p->n_pairs;
@@ -122,7 +128,7 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
   size_t off = align(sizeof(WsHeader));
   L->off_pairs = off;       off = align(off + sizeof(DevPair) * (size_t)std::max(1, p->n_pairs));
-  L->off_fwd_items = off;   off = align(off + sizeof(FwdItem) * (size_t)std::max<int64_t>(1, L->n_fwd_items));
+  L->off_fwd_items = off;   off = align(off + sizeof(QItem) * (size_t)std::max<int64_t>(1, L->n_fwd_items));
   L->off_bwd_deps = off;    off = align(off + sizeof(BwdDep) * (size_t)std::max<int64_t>(1, L->n_bwd_deps));
   L->off_bwd_items = off;   off = align(off + sizeof(BwdItem) * (size_t)std::max<int64_t>(1, L->n_bwd_items));
   L->off_merge_items = off; off = align(off + sizeof(MergeItem) * (size_t)std::max<int64_t>(1, L->n_merge_items));
@@ -306,9 +312,10 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     dpairs[i] = {kb.tok_start, kb.tok_len, p->pairs[i].kind, 0};
   }
   const int G = p->n_q_heads / p->n_kv_heads;
-  // ---- forward: one group per (slot, KV head): its query tiles x the G query heads share K/V.
+  // ---- forward: one group per (slot, KV head): its items share K/V.  An item joins two sub-tiles:
+  // heads (2j, 2j+1) of the group on one row tile when G is even, else row tiles (2j, 2j+1) of one head.
   {
-    std::vector<std::vector<FwdItem>> groups;
+    std::vector<std::vector<QItem>> groups;
     std::vector<int64_t> weight;
     groups.reserve((size_t)p->n_slots * p->n_kv_heads);
     for (int s = 0; s < p->n_slots; s++) {
@@ -325,26 +332,43 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
           tile_w[t] += (int64_t)rows * cols;
         }
       }
+      auto sub = [&](QItem* it, int k, int t, int head) {
+        const int off = t * L.fwd_tile_m;
+        it->q_start[k] = qb.tok_start + off; it->q_rows[k] = std::min(L.fwd_tile_m, qb.tok_len - off);
+        it->out_row[k] = sl.row_start + off; it->tile_off[k] = off; it->head[k] = head;
+      };
       for (int g = 0; g < p->n_kv_heads; g++) {
-        std::vector<FwdItem> items;
+        std::vector<QItem> items;
         int64_t w = 0;
-        for (int t = n_tiles - 1; t >= 0; t--) {       // later tiles of a DIAG pair are heavier
-          const int off = t * L.fwd_tile_m;
-          const int rows = std::min(L.fwd_tile_m, qb.tok_len - off);
-          for (int hh = 0; hh < G; hh++) {
-            items.push_back({qb.tok_start + off, rows, sl.row_start + off, off, sl.pair_begin, sl.n_pairs,
-                             g * G + hh, 0});
-            w += tile_w[t];
-          }
+        if (G % 2 == 0) {
+          for (int t = n_tiles - 1; t >= 0; t--)         // later tiles of a DIAG pair are heavier
+            for (int hh = 0; hh < G; hh += 2) {
+              QItem it{};
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs;
+              sub(&it, 0, t, g * G + hh); sub(&it, 1, t, g * G + hh + 1);
+              items.push_back(it);
+              w += 2 * tile_w[t];
+            }
+        } else {
+          for (int t = n_tiles - 1; t >= 0; t -= 2)
+            for (int hh = 0; hh < G; hh++) {
+              QItem it{};
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs;
+              sub(&it, 0, t, g * G + hh);
+              if (t >= 1) { sub(&it, 1, t - 1, g * G + hh); w += tile_w[t - 1]; }
+              else { it.q_start[1] = it.q_start[0]; it.q_rows[1] = 0; it.out_row[1] = it.out_row[0]; it.tile_off[1] = it.tile_off[0]; it.head[1] = it.head[0]; }
+              items.push_back(it);
+              w += tile_w[t];
+            }
         }
         groups.push_back(std::move(items));
         weight.push_back(w);
       }
     }
-    std::vector<FwdItem> flat;
+    std::vector<QItem> flat;
     spread_over_xcds(groups, weight, &flat, hdr->fwd_begin);
     if ((int64_t)flat.size() != L.n_fwd_items) { set_error("internal: forward item count mismatch"); return FCP_ERR_INVALID_ARG; }
-    if (!flat.empty()) std::memcpy(host.data() + L.off_fwd_items, flat.data(), flat.size() * sizeof(FwdItem));
+    if (!flat.empty()) std::memcpy(host.data() + L.off_fwd_items, flat.data(), flat.size() * sizeof(QItem));
   }
   // ---- backward: dependency lists per KV block, one group per (KV block, KV head).
   {

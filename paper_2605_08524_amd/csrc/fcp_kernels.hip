@@ -197,20 +197,28 @@ __device__ __forceinline__ void retire(int32_t* counter, int32_t* done) {
 }
 
 // =====================================================================================
-// Forward: partial attention of one (slot, 128-row query tile, query head) item.
+// Forward: partial attention.  Item = (slot, two 128-row query sub-tiles that share the slot's
+// K/V stream: two query heads of one KV head, or two neighbouring row tiles of one head);
+// workgroup of 8 waves, two per SIMD, 32 query rows per wave.
 // The wave computes S^T = K Q^T so that a lane owns one query row (column of S^T): row
 // statistics need one cross-half exchange, and the exponentiated accumulator is, as is,
-// the B operand of O^T += V^T P^T.  K/V tiles of 64 rows are double-buffered in LDS and
-// filled by LDS-DMA one tile ahead; two workgroups per CU (two waves per SIMD) let one wave's
-// softmax overlap the other's MFMAs.
+// the B operand of O^T += V^T P^T.  The loop over 64-row K/V tiles is software-pipelined by
+// hand: in iteration i the wave issues the MFMAs of S(i+1) and then of O += V(i)^T P(i), and
+// places the exponentials of tile i, and later the maximum of tile i+1, between them, so the
+// matrix pipe does not wait for the vector ALU inside a wave.  [K | V] tiles sit in a ring of
+// four LDS buffers filled by LDS-DMA three tiles ahead (all 8 waves share one stream); one
+// workgroup barrier per tile.  Iterations before the first and past the last tile of an item
+// run on fully masked scores (P = 0), so every iteration is the same instruction stream, and
+// the ring runs on from item to item.
 // =====================================================================================
 constexpr int kFwdTileN = 64;   // KV rows per LDS tile
+constexpr int kFwdBufs = 4;     // ring of [K | V] tile buffers
 constexpr float kRescaleSlack = 8.0f;   // log2 units
 
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
   float* o_part; float* lse_part;
-  WsHeader* hdr; const DevPair* pairs; const FwdItem* items;
+  WsHeader* hdr; const DevPair* pairs; const QItem* items;
   int32_t n_q_heads, n_kv_heads;
   float scale_log2;   // softmax scale * log2(e)
 };
@@ -242,62 +250,81 @@ struct TileIter {
   }
 };
 
+// What a wave needs to know about a tile when it masks it: first column, visible length, kind.
+// A tile past the end of the item has len = 0: everything is masked.
+struct TileMeta { int c0, len, diag; };
+
 template <int D>
-__global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
+__global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
   constexpr int KC = D / 16;      // k-chunks of the QK^T contraction
   constexpr int DT = D / 32;      // row tiles of O^T
+  constexpr int NS1 = 2 * KC;     // MFMAs of S^T (two 32-row halves of the KV tile)
+  constexpr int NS2 = 4 * DT;     // MFMAs of O^T += V^T P^T
+  constexpr int PF = 4;           // an LDS operand is requested this many MFMAs before its use
   constexpr int TB = tile_bytes<D>(kFwdTileN);
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_k[2][TB];
-  __shared__ __attribute__((aligned(1024))) unsigned char lds_v[2][TB];
+  constexpr int BUF = 2 * TB;     // [K tile | V tile]
+  constexpr int NB = kFwdBufs;
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NDMA = kFwdTileN / RPI / 8;   // LDS-DMA geometry, see issue()
+  constexpr int DMA_PER_TILE = 2 * NDMA;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_kv[NB][BUF];
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+  const int sub = wave >> 2, wq = wave & 3;                    // sub-item, 32-row group inside it
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;     // elements
   const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
   const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
-  const uint32_t dma_off = dma_lane_offset<D>(wave, lane, kv_row_stride);
+  // LDS-DMA of a 64-row tile: instruction n of this wave fills LDS rows r_n = (8n + wave) * RPI + lane / CPR.
+  // A lane fetches chunk (pc ^ swz(r_n)) of global row min(r_n, valid - 1): rows past a ragged end
+  // repeat the last valid row (finite values; those columns are masked).
+  uint32_t dma_row[NDMA], dma_chunk[NDMA];
+#pragma unroll
+  for (int n = 0; n < NDMA; n++) {
+    const int r = (8 * n + wave) * RPI + lane / CPR, pc = lane % CPR;
+    dma_row[n] = (uint32_t)(r * kv_row_stride * 2);
+    dma_chunk[n] = (uint32_t)((pc ^ swz<D>(r)) << 4);
+  }
   // transpose-read pattern inside a 16-lane group: row tr_row, 4 columns from tr_col
   const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  // Per-lane LDS addresses into the CURRENT buffer (the swizzle has period 16 in the row, so
-  // rows +16 / +32 are plain immediate offsets); switched in place after every tile.
+  for (int i = tid * 16; i < NB * BUF; i += 512 * 16)
+    *reinterpret_cast<u32x4*>(&lds_kv[0][0] + i) = u32x4{0, 0, 0, 0};
+  // Ring positions, advanced by one buffer per tile and kept across items: in iteration i the
+  // wave reads the K rows of tile i+1 (b_k), transposes V of tile i (b_v), and tile i+3 is requested (b_dma).
+  int b_k = 0, b_v = NB - 1, b_dma = 2;
+  // Per-lane LDS addresses into the current buffers (the swizzle has period 16 in the row, so
+  // rows +16 / +32 are plain immediate offsets), advanced in place.
   uint32_t tr_lo[DT], tr_hi[DT], kk_off[KC];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++) {
-    tr_lo[dt] = lds_addr(lds_v[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-    tr_hi[dt] = lds_addr(lds_v[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_lo[dt] = lds_addr(lds_kv[b_v]) + TB + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = lds_addr(lds_kv[b_v]) + TB + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
   }
 #pragma unroll
-  for (int kc = 0; kc < KC; kc++) kk_off[kc] = lds_addr(lds_k[0]) + tile_off<D>(l32, 2 * kc + g);
-  int buf = 0;                              // buffer the addresses above point into
-  auto switch_buffer = [&]() {
-    const int step = buf ? -TB : TB;
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += step; tr_hi[dt] += step; }
-#pragma unroll
-    for (int kc = 0; kc < KC; kc++) kk_off[kc] += step;
-    buf ^= 1;
-  };
+  for (int kc = 0; kc < KC; kc++) kk_off[kc] = lds_addr(lds_kv[b_k]) + tile_off<D>(l32, 2 * kc + g);
+  __syncthreads();
 
   for (;;) {
     if (tid == 0) s_item = pop_item(a.hdr->fwd_counter, a.hdr->fwd_begin);
     __syncthreads();
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
-    const FwdItem it = a.items[item_idx];
-    const int kvh = it.head / group;
-    const int my_row = wave * 32 + l32;                      // row inside the tile
-    const bool row_ok = my_row < it.q_rows;
-    const int wave_row_lo = it.tile_off + wave * 32;         // rows of this wave inside the block
+    const QItem it = a.items[item_idx];
+    const int q_rows = it.q_rows[sub], tile_off_q = it.tile_off[sub], head = it.head[sub];
+    const int kvh = it.head[0] / group;
+    const int my_row = wq * 32 + l32;                        // row inside the sub-tile
+    const bool row_ok = my_row < q_rows;
+    const int wave_row_lo = tile_off_q + wq * 32;            // rows of this wave inside the block
+    const int my_limit = tile_off_q + my_row;                // last visible column of a DIAG pair for this lane
     const uint16_t* kbase = a.k + (int64_t)kvh * D;
     const uint16_t* vbase = a.v + (int64_t)kvh * D;
 
     // Q^T fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d per k-chunk.
     bf16x8 qf[KC];
     {
-      const uint16_t* qp = a.q + (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D + 8 * g;
+      const uint16_t* qp = a.q + (int64_t)(it.q_start[sub] + my_row) * q_row_stride + (int64_t)head * D + 8 * g;
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) {
         u32x4 v = {0, 0, 0, 0};
@@ -312,139 +339,177 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
       for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
+    // number of tiles of the item, and of iterations: tiles + 1 (pipeline fill), rounded up to even
     TileIter ti;                      // names the next tile to LOAD
-    ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
-    auto dma = [&](int buf) {
-      const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
-      tile_dma<D, kFwdTileN, 4>(lds_k[buf], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
-      tile_dma<D, kFwdTileN, 4>(lds_v[buf], vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
+    int n_it = 1;
+    for (int p = 0; p < it.n_pairs; p++) {
+      const DevPair pr = a.pairs[it.pair_begin + p];
+      const int nc = pr.kind == FCP_KIND_DIAG ? min(pr.kv_len, ti.row_hi) : pr.kv_len;
+      n_it += (nc + kFwdTileN - 1) / kFwdTileN;
+    }
+    n_it = (n_it + 1) & ~1;
+
+    // The load of one tile in two parts.  describe(): scalar bookkeeping with branches, run at
+    // an iteration boundary.  issue(): branch-free, sits between the MFMAs.
+    uint64_t d_k = 0, d_v = 0;
+    uint32_t d_lim = 0;
+    TileMeta d_meta = {0, 0, 0};
+    auto describe = [&]() {
+      d_k = reinterpret_cast<uint64_t>(zeros); d_v = d_k; d_lim = 0; d_meta = TileMeta{0, 0, 0};
+      if (ti.more) {
+        const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
+        d_k = reinterpret_cast<uint64_t>(kbase + row0);
+        d_v = reinterpret_cast<uint64_t>(vbase + row0);
+        const int valid = min(kFwdTileN, ti.cur.kv_len - ti.c0);
+        d_lim = (uint32_t)((valid - 1) * kv_row_stride * 2);
+        d_meta = TileMeta{ti.c0, ti.cur.kv_len, ti.cur.kind == FCP_KIND_DIAG ? 1 : 0};
+        ti.advance();
+      }
     };
-    DevPair tp = ti.cur;              // the tile being computed
-    int tc0 = 0;
-    bool have = ti.more;              // an empty slot yields O = 0, LSE = -inf
-    if (have) { dma(buf); ti.advance(); }
+    auto issue = [&]() {
+      const uint32_t lbase = lds_addr(lds_kv[0]) + b_dma * BUF;
+#pragma unroll
+      for (int n = 0; n < NDMA; n++) {
+        const uint32_t voff = min(dma_row[n], d_lim) + dma_chunk[n];
+        lds_dma16_s(reinterpret_cast<const unsigned char*>(d_k), voff, lbase + (8 * n + wave) * 1024);
+        lds_dma16_s(reinterpret_cast<const unsigned char*>(d_v), voff, lbase + TB + (8 * n + wave) * 1024);
+      }
+      b_dma = (b_dma == NB - 1) ? 0 : b_dma + 1;
+    };
+    // prologue: tiles 0 and 1 into the two buffers before the next one to load
+    TileMeta meta[3];                 // tiles i+1, i+2, i+3 (shift register)
+    b_dma = (b_dma + NB - 2) % NB;
+    describe(); issue(); meta[0] = d_meta;
+    describe(); issue(); meta[1] = d_meta;
+    describe(); meta[2] = d_meta;     // tile 2, requested inside the first iteration
     dma_wait();
     __syncthreads();
-    while (have) {
-      // next tile into the other buffer (its readers finished before the last barrier)
-      const DevPair np = ti.cur;
-      const int nc0 = ti.c0;
-      const bool nhave = ti.more;
-      if (nhave) { dma(buf ^ 1); ti.advance(); }
 
-      const bool diag = tp.kind == FCP_KIND_DIAG;
-      // a wave whose rows all lie above this tile's first column has nothing visible in it
-      if (!(diag && tc0 > wave_row_lo + 31)) {
-        // ---- S^T = K Q^T  (two 32-row tiles of KV).  The K fragments of k-chunk kc+1 are requested
-        // before the MFMAs of chunk kc are issued, so the LDS latency hides behind them.
-        f32x16 s[2];
+    f32x16 s_a[2], s_b[2];            // S^T of the tile being exponentiated / being computed
 #pragma unroll
-        for (int rt = 0; rt < 2; rt++)
+    for (int rt = 0; rt < 2; rt++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) s[rt][r] = 0.f;
-        {
-          constexpr int PF = 2;                      // stages (of two MFMAs) requested ahead
-          u32x4 kfr[PF + 1][2];
+      for (int r = 0; r < 16; r++) { s_a[rt][r] = -INFINITY; s_b[rt][r] = 0.f; }
+
+    // One iteration.  sc = scores of tile i (masked, maximum already folded into m_run);
+    // sn receives S^T of tile i+1.
+    auto iteration = [&](f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+      u32x4 pb[4];                    // P^T of tile i as four B operands (rt, j)
+      float rs = 0.f;
+      float p_prev = 0.f;
+      auto expo = [&](int e) {        // element e = (rt, r) of tile i
+        const int rt = e >> 4, r = e & 15;
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[rt][r], a.scale_log2, -m_use));
+        rs += p;
+        if (r & 1) {
+          pb[e >> 3][(e >> 1) & 3] = pack_bf16(p_prev, p);
+          // keeps the vector work between the MFMAs it was written between
+          asm volatile("" :: "v"(pb[e >> 3][(e >> 1) & 3]));
+        } else p_prev = p;
+      };
+      // ---- phase 1: S^T(i+1) = K Q^T (two 32-row halves); exponentials of tile i between the MFMAs
+      {
+        u32x4 op[PF];
 #pragma unroll
-          for (int p = 0; p < PF; p++)
+        for (int u = 0; u < PF; u++) op[u] = lds_read16(kk_off[u / 2] + (u & 1) * 32 * (D * 2));
 #pragma unroll
-            for (int rt = 0; rt < 2; rt++)
-              kfr[p][rt] = lds_read16(kk_off[p] + rt * 32 * (D * 2));
+        for (int u = 0; u < NS1; u++) {
+          const int kc = u / 2, rt = u & 1;
+          if (kc == 0) {
 #pragma unroll
-          for (int kc = 0; kc < KC; kc++) {
-            if (kc + PF < KC) {
-#pragma unroll
-              for (int rt = 0; rt < 2; rt++)
-                kfr[(kc + PF) % (PF + 1)][rt] = lds_read16(kk_off[kc + PF] + rt * 32 * (D * 2));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int rt = 0; rt < 2; rt++)
-              s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kfr[kc % (PF + 1)][rt]), qf[kc], s[rt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 16; r++) sn[rt][r] = 0.f;
           }
-        }
-        // ---- mask (only tiles that touch the diagonal or the ragged end)
-        const bool need_mask = (tc0 + kFwdTileN > tp.kv_len) || (diag && tc0 + kFwdTileN - 1 > wave_row_lo);
-        if (need_mask) {
-          const int limit = diag ? min(tp.kv_len - 1, it.tile_off + my_row) : tp.kv_len - 1;   // last visible column
+          sn[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), qf[kc], sn[rt], 0, 0, 0);
+          if (u + PF < NS1) op[u % PF] = lds_read16(kk_off[(u + PF) / 2] + ((u + PF) & 1) * 32 * (D * 2));
+          // 24 of the 32 elements in this phase
 #pragma unroll
-          for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-              const int col = tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-              if (col > limit) s[rt][r] = -INFINITY;
-            }
-        }
-        // ---- online softmax in the log2 domain.  The reference maximum m_run only moves when some
-        // row's maximum exceeds it by more than kRescaleSlack (a wave-uniform decision): any reference
-        // gives the same O and LSE as long as exp2 stays in range, and P <= 2^slack is harmless in
-        // bf16/fp32.  Most tiles therefore skip the rescaling of the O accumulators.
-        float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-        for (int r = 1; r < 16; r++) mx = fmaxf(fmaxf(mx, s[0][r]), s[1][r]);
-        mx = fmaxf(mx, xor32(mx)) * a.scale_log2;
-        if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-          const float m_new = fmaxf(m_run, mx);
-          const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // m_run = -inf -> 0
-          m_run = m_new;
-          l_run *= alpha;
-#pragma unroll
-          for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
-        }
-        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-        float rs = 0.f;
-#pragma unroll
-        for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rt][r], a.scale_log2, -m_use));
-            s[rt][r] = p;
-            rs += p;
-          }
-        l_run += rs;
-        // ---- O^T += V^T P^T ; P^T's accumulator registers are its B operand.  The V^T fragment of
-        // the next MFMA is requested before the current MFMA is issued.
-        {
-          u32x4 pb[4];
-#pragma unroll
-          for (int rt = 0; rt < 2; rt++)
-#pragma unroll
-            for (int j = 0; j < 2; j++)
-#pragma unroll
-              for (int i = 0; i < 4; i++) pb[rt * 2 + j][i] = pack_bf16(s[rt][8 * j + 2 * i], s[rt][8 * j + 2 * i + 1]);
-          constexpr int PF = 3;                      // MFMAs requested ahead
-          constexpr int NU = 4 * DT;                 // u = (rt, j, dt)
-          bf16x8 vfr[PF + 1];
-          auto fetch = [&](int u) {
-            const uint32_t rows = 16 * (u / DT) * (D * 2);
-            return lds_tr_pair_at(tr_lo[u % DT] + rows, tr_hi[u % DT] + rows);
-          };
-#pragma unroll
-          for (int p = 0; p < PF; p++) vfr[p] = fetch(p);
-#pragma unroll
-          for (int u = 0; u < NU; u++) {
-            if (u + PF < NU) vfr[(u + PF) % (PF + 1)] = fetch(u + PF);
-            __builtin_amdgcn_sched_barrier(0);
-            o[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[u % (PF + 1)], as_bf16x8(pb[u / DT]), o[u % DT], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+          for (int e = u * 24 / NS1; e < (u + 1) * 24 / NS1; e++) expo(e);
+          if (u == NS1 / 2) issue();
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-      tp = np; tc0 = nc0; have = nhave;
-      dma_wait();
+      // ---- phase 2: O^T += V^T P^T; the rest of the exponentials
+      {
+        u32x4 op[PF];
+        auto fetch = [&](int u) {
+          const uint32_t rows = 16 * (u / DT) * (D * 2);
+          return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo[u % DT] + rows, tr_hi[u % DT] + rows));
+        };
+#pragma unroll
+        for (int u = 0; u < PF; u++) op[u] = fetch(u);
+#pragma unroll
+        for (int u = 0; u < NS2; u++) {
+          o[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), as_bf16x8(pb[u / DT]), o[u % DT], 0, 0, 0);
+          if (u + PF < NS2) op[u % PF] = fetch(u + PF);
+#pragma unroll
+          for (int e = 24 + u * 8 / (NS2 / 2); e < 24 + (u + 1) * 8 / (NS2 / 2) && u < NS2 / 2; e++) expo(e);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      l_run += rs;
+      // the tile two ahead has landed once at most one tile's loads are in flight
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (DMA_PER_TILE & 15) | ((DMA_PER_TILE >> 4) << 14));
       __syncthreads();
-      switch_buffer();
+      // ---- mask of tile i+1 (only tiles that touch the diagonal or a ragged end, or lie past the
+      // end of the item), then its maximum
+      {
+        const TileMeta tm = meta[0];
+        if (tm.len == 0 || tm.c0 + kFwdTileN > tm.len || (tm.diag && tm.c0 + kFwdTileN - 1 > wave_row_lo)) {
+          // last visible column for this lane, relative to the tile's first column
+          const int limit = (tm.diag ? min(tm.len - 1, my_limit) : tm.len - 1) - tm.c0 - 4 * g;
+#pragma unroll
+          for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+              if (rt * 32 + 8 * (r >> 2) + (r & 3) > limit) sn[rt][r] = -INFINITY;
+        }
+      }
+      float mx = fmaxf(sn[0][0], sn[1][0]);
+#pragma unroll
+      for (int r = 1; r < 16; r++) mx = fmaxf(fmaxf(mx, sn[0][r]), sn[1][r]);
+      // ---- online softmax bookkeeping for tile i+1, in the log2 domain.  The reference maximum
+      // m_run only moves when some row's maximum exceeds it by more than kRescaleSlack (a
+      // wave-uniform decision): any reference gives the same O and LSE as long as exp2 stays in
+      // range, and P <= 2^slack is harmless in bf16/fp32.  Most tiles skip the rescaling of O.
+      mx = fmaxf(mx, xor32(mx)) * a.scale_log2;
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // m_run = -inf -> 0
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+      }
+      // ---- rotate the ring
+      meta[0] = meta[1]; meta[1] = meta[2];
+      describe(); meta[2] = d_meta;
+      {
+        const int sk = (b_k == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+        for (int kc = 0; kc < KC; kc++) kk_off[kc] += sk;
+        b_k = (b_k == NB - 1) ? 0 : b_k + 1;
+        const int sv = (b_v == NB - 1) ? -(NB - 1) * BUF : BUF;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += sv; tr_hi[dt] += sv; }
+        b_v = (b_v == NB - 1) ? 0 : b_v + 1;
+      }
+    };
+    for (int i = 0; i < n_it; i += 2) {
+      iteration(s_a, s_b);
+      iteration(s_b, s_a);
     }
+    dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
 
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
     const float l_tot = l_run + xor32(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (row_ok) {
-      float* op = a.o_part + (int64_t)(it.out_row + my_row) * q_row_stride + (int64_t)it.head * D;
+      float* op = a.o_part + (int64_t)(it.out_row[sub] + my_row) * q_row_stride + (int64_t)head * D;
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -454,7 +519,7 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(FwdArgs a) {
         }
       if (g == 0) {
         const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-        a.lse_part[(int64_t)(it.out_row + my_row) * a.n_q_heads + it.head] = lse;
+        a.lse_part[(int64_t)(it.out_row[sub] + my_row) * a.n_q_heads + head] = lse;
       }
     }
     __syncthreads();   // s_item is rewritten next
@@ -1163,7 +1228,7 @@ static float resolve_scale(const fcp_problem* p) {
   return p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
 }
 
-constexpr int kFwdWgPerCu = 2;
+constexpr int kFwdWgPerCu = 1;   // 8 waves, two per SIMD
 constexpr int kDkdvWgPerCu = 1;   // 8 waves, two per SIMD
 constexpr int kDqWgPerCu = 2;
 
@@ -1194,12 +1259,12 @@ extern "C" int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const voi
   a.o_part = o_part; a.lse_part = lse_part;
   a.hdr = reinterpret_cast<WsHeader*>(ws);
   a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);
-  a.items = reinterpret_cast<const FwdItem*>(ws + L.off_fwd_items);
+  a.items = reinterpret_cast<const QItem*>(ws + L.off_fwd_items);
   a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.scale_log2 = resolve_scale(p) * kLog2e;
-  const int grid = (int)std::min<int64_t>(L.n_fwd_items, (int64_t)cu_count() * kFwdWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(fwd_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(fwd_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  int grid = (int)std::min<int64_t>(L.n_fwd_items, (int64_t)cu_count() * kFwdWgPerCu);
+  if (p->head_dim == 128) hipLaunchKernelGGL(fwd_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(fwd_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch("fcp_block_attn_fwd");
 }
 
