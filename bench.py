@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload: 5 = training step (default), 2/3/4 = forward only")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-step", action="store_true",
+                    help="every query block goes through the partial buffers and the merge, also those with one slot")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
@@ -97,7 +99,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2605_08524_amd import FCP_FLAG_O_F32, fcp_device_info, workloads
+    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, fcp_device_info, workloads
     from paper_2605_08524_amd.harness import DevicePath
 
     dev = torch.device("cuda:0")
@@ -106,7 +108,9 @@ def main():
     backward = args.config == 5
     stream = torch.cuda.current_stream(dev)
     t0 = time.perf_counter()
-    dp = DevicePath(wl, dev, flags=FCP_FLAG_O_F32 if backward else 0, backward=backward, stream=stream)
+    # a query block with one slot needs no reduction: the forward writes it straight to the final O / LSE
+    flags = (0 if args.two_step else FCP_FLAG_DIRECT_SINGLE) | (FCP_FLAG_O_F32 if backward else 0)
+    dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream)
     torch.cuda.synchronize(dev)
     setup_s = time.perf_counter() - t0
     f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
@@ -158,8 +162,15 @@ def main():
     dom = max(cands, key=lambda k: stage_ms[k])
     achieved = kernel_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
     p = dp.problem
-    merge_bytes = (p.n_slot_rows * wl.n_q_heads * (wl.head_dim * 4 + 4)
-                   + p.t_q * wl.n_q_heads * (wl.head_dim * (4 if backward else 2) + 4))
+    # the merge touches only query blocks with several slots (the others were written by the forward)
+    import numpy as np
+    slots, qb = dp.plan["slots"], dp.plan["q_blocks"]
+    cnt = np.bincount(slots[:, 0], minlength=len(qb)) if len(slots) else np.zeros(len(qb), dtype=np.int64)
+    merged = cnt > (1 if (flags & FCP_FLAG_DIRECT_SINGLE) else 0)
+    merged_rows = int(qb[merged, 3].sum()) if len(qb) else 0
+    part_rows = int((cnt[merged] * qb[merged, 3]).sum()) if len(qb) else 0
+    merge_bytes = (part_rows * wl.n_q_heads * (wl.head_dim * 4 + 4)
+                   + merged_rows * wl.n_q_heads * (wl.head_dim * (4 if backward else 2) + 4))
     info = fcp_device_info()
     out = {
         "metric": "block-attention fwd+bwd TFLOP/s (causal-adj)" if backward else "block-attention fwd TFLOP/s (causal-adj)",
@@ -179,7 +190,8 @@ def main():
         "frac_of_bf16_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "kernel_tflops": {k: round(kernel_flops[k] / stage_ms[k] / 1e9, 2) for k in cands},
-        "merge_gbs": round(merge_bytes / stage_ms["merge"] / 1e6, 1),
+        "merge_gbs": round(merge_bytes / stage_ms["merge"] / 1e6, 1) if merge_bytes else None,
+        "merged_query_rows": merged_rows,
         "roofline": {
             "kernel": kernel_name[dom],
             "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -53,7 +53,11 @@ typedef struct { int32_t q_blk, kv_blk, kind, slot; } fcp_pair;
 typedef struct { int32_t q_blk, pair_begin, n_pairs, row_start; } fcp_slot;
 
 enum {
-  FCP_FLAG_O_F32 = 1             /* fcp_merge_partials writes fp32 O instead of bf16 (bwd then reads fp32 O) */
+  FCP_FLAG_O_F32 = 1,            /* the final O is fp32 instead of bf16 (the backward then reads fp32 O) */
+  FCP_FLAG_DIRECT_SINGLE = 2     /* a query block with ONE slot needs no reduction: fcp_block_attn_fwd_out writes its
+                                    result straight to the final o / lse and fcp_merge_partials leaves it alone.
+                                    Set it before fcp_workspace_bytes / fcp_queue_build and keep it for every call
+                                    on that workspace; with it, call fcp_block_attn_fwd_out, not fcp_block_attn_fwd. */
 };
 
 /* Problem descriptor.  All table pointers are HOST pointers to tables produced by
@@ -136,12 +140,28 @@ int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const
                        float* o_part, float* lse_part, void* workspace, void* stream);
 
 /*
+ * fcp_block_attn_fwd_out -- fcp_block_attn_fwd that also knows the final outputs.
+ *
+ * Paper: section "Context Parallelism": the per-stage results of a query block are reduced to
+ * its final output; with a single stage the reduction is the identity.  With
+ * FCP_FLAG_DIRECT_SINGLE set, the slot of a query block that has exactly one slot is written
+ * to o / lse (rows tok_start .. of the query block; dtype of o per FCP_FLAG_O_F32) instead of
+ * the partial buffers, whose rows for that slot are left untouched; all other slots go to
+ * o_part / lse_part as in fcp_block_attn_fwd.  Without the flag it behaves exactly like
+ * fcp_block_attn_fwd and ignores o / lse.  o [T_q,Hq,d], lse [T_q,Hq]: device.
+ */
+int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, const void* v,
+                           float* o_part, float* lse_part, void* o, float* lse,
+                           void* workspace, void* stream);
+
+/*
  * fcp_merge_partials -- reduce the partials of each query block to the final output.
  *
  * Paper: section "Context Parallelism" (intermediate results over slices are reduced to the
  * final outputs).  LSE = ln sum_p exp(LSE_p); O = sum_p exp(LSE_p - LSE) O_p; exp(-inf) = 0;
  * a row with only empty partials gets O = 0, LSE = -inf.
  * o [T_q,Hq,d]: device, bf16 (default) or fp32 (FCP_FLAG_O_F32); lse [T_q,Hq]: device fp32.
+ * With FCP_FLAG_DIRECT_SINGLE, query blocks with one slot are skipped (fcp_block_attn_fwd_out wrote them).
  */
 int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* lse_part,
                        void* o, float* lse, void* workspace, void* stream);

@@ -23,9 +23,10 @@ FCP_ERR_UNSUPPORTED = -3
 FCP_ERR_HIP = -4
 FCP_KIND_FULL, FCP_KIND_DIAG = 0, 1
 FCP_FLAG_O_F32 = 1
+FCP_FLAG_DIRECT_SINGLE = 2
 
 EXPORTS = (
-    "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd",
+    "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_last_error", "fcp_device_info",
 )
@@ -59,6 +60,7 @@ def _load():
     lib.fcp_workspace_bytes.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_size_t)]
     lib.fcp_queue_build.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
+    lib.fcp_block_attn_fwd_out.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 9
     lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
     lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
@@ -132,6 +134,7 @@ class Problem:
         self.pairs = _i32(plan["pairs"]).reshape(-1, 4)
         self.slots = _i32(plan["slots"]).reshape(-1, 4)
         self.n_slot_rows = int(plan["n_slot_rows"])
+        self.flags = int(flags)
         self.n_q_heads, self.n_kv_heads, self.head_dim = int(n_q_heads), int(n_kv_heads), int(head_dim)
         self.t_q = int(self.q_blocks[:, 3].sum()) if len(self.q_blocks) else 0
         self.t_kv = int(self.kv_blocks[:, 3].sum()) if len(self.kv_blocks) else 0
@@ -161,6 +164,11 @@ def fcp_queue_build(problem: Problem, workspace, workspace_bytes, stream=None):
 def fcp_block_attn_fwd(problem: Problem, q, k, v, o_part, lse_part, workspace, stream=None):
     _check(_lib.fcp_block_attn_fwd(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o_part), _ptr(lse_part),
                                    _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_fwd_out(problem: Problem, q, k, v, o_part, lse_part, o, lse, workspace, stream=None):
+    _check(_lib.fcp_block_attn_fwd_out(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o_part), _ptr(lse_part),
+                                       _ptr(o), _ptr(lse), _ptr(workspace), _stream(stream)))
 
 
 def fcp_merge_partials(problem: Problem, o_part, lse_part, o, lse, workspace, stream=None):

@@ -115,8 +115,12 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   for (int b = 0; b < p->n_kv_blocks; b++)
     L->n_bwd_items += ceil_div(p->kv_blocks[b].tok_len, kBwdTileN) * p->n_kv_heads;
   L->n_bwd_deps = p->n_pairs;
+  std::vector<int32_t> slots_of(p->n_q_blocks, 0);
+  for (int s = 0; s < p->n_slots; s++) slots_of[p->slots[s].q_blk]++;
+  const bool direct = (p->flags & FCP_FLAG_DIRECT_SINGLE) != 0;
   for (int b = 0; b < p->n_q_blocks; b++) {
-    L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
+    if (!(direct && slots_of[b] == 1))
+      L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
     L->n_dq_items += ceil_div(p->q_blocks[b].tok_len, kFwdTileM) * p->n_q_heads;
     L->t_q += p->q_blocks[b].tok_len;
   }
@@ -318,6 +322,8 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     std::vector<std::vector<QItem>> groups;
     std::vector<int64_t> weight;
     groups.reserve((size_t)p->n_slots * p->n_kv_heads);
+    std::vector<int32_t> n_slots_of(p->n_q_blocks, 0);
+    for (int s = 0; s < p->n_slots; s++) n_slots_of[p->slots[s].q_blk]++;
     for (int s = 0; s < p->n_slots; s++) {
       const fcp_slot& sl = p->slots[s];
       const fcp_block& qb = p->q_blocks[sl.q_blk];
@@ -332,6 +338,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
           tile_w[t] += (int64_t)rows * cols;
         }
       }
+      const int to_final = ((p->flags & FCP_FLAG_DIRECT_SINGLE) && n_slots_of[sl.q_blk] == 1) ? 1 : 0;
       auto sub = [&](QItem* it, int k, int t, int head) {
         const int off = t * L.fwd_tile_m;
         it->q_start[k] = qb.tok_start + off; it->q_rows[k] = std::min(L.fwd_tile_m, qb.tok_len - off);
@@ -344,7 +351,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
           for (int t = n_tiles - 1; t >= 0; t--)         // later tiles of a DIAG pair are heavier
             for (int hh = 0; hh < G; hh += 2) {
               QItem it{};
-              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs;
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.pad[0] = to_final;
               sub(&it, 0, t, g * G + hh); sub(&it, 1, t, g * G + hh + 1);
               items.push_back(it);
               w += 2 * tile_w[t];
@@ -353,7 +360,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
           for (int t = n_tiles - 1; t >= 0; t -= 2)
             for (int hh = 0; hh < G; hh++) {
               QItem it{};
-              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs;
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.pad[0] = to_final;
               sub(&it, 0, t, g * G + hh);
               if (t >= 1) { sub(&it, 1, t - 1, g * G + hh); w += tile_w[t - 1]; }
               else { it.q_start[1] = it.q_start[0]; it.q_rows[1] = 0; it.out_row[1] = it.out_row[0]; it.tile_off[1] = it.tile_off[0]; it.head[1] = it.head[0]; }
@@ -479,6 +486,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     int64_t n = 0;
     for (int b = 0; b < p->n_q_blocks; b++) {
       const fcp_block& qb = p->q_blocks[b];
+      if ((p->flags & FCP_FLAG_DIRECT_SINGLE) && slot_begin[b + 1] - slot_begin[b] == 1) continue;   // written by the forward
       const int64_t total = (int64_t)qb.tok_len * p->n_q_heads;
       for (int64_t off = 0; off < total; off += kMergeChunk) {
         mi[n++] = {(int32_t)((int64_t)qb.tok_start * p->n_q_heads + off), (int32_t)std::min<int64_t>(kMergeChunk, total - off),

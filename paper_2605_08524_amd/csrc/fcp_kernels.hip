@@ -218,6 +218,7 @@ constexpr float kRescaleSlack = 8.0f;   // log2 units
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
   float* o_part; float* lse_part;
+  void* o; float* lse; int32_t o_is_f32;     // final outputs for query blocks with a single slot (or NULL)
   WsHeader* hdr; const DevPair* pairs; const QItem* items;
   int32_t n_q_heads, n_kv_heads;
   float scale_log2;   // softmax scale * log2(e)
@@ -509,17 +510,32 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     const float l_tot = l_run + xor32(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (row_ok) {
-      float* op = a.o_part + (int64_t)(it.out_row[sub] + my_row) * q_row_stride + (int64_t)head * D;
+      // the only slot of its query block: this is the final result, not a partial
+      const bool to_final = it.pad[0] != 0;
+      const int64_t row = to_final ? (int64_t)(it.q_start[sub] + my_row) : (int64_t)(it.out_row[sub] + my_row);
+      const int64_t off = row * q_row_stride + (int64_t)head * D;
+      if (to_final && !a.o_is_f32) {
+        uint16_t* op = reinterpret_cast<uint16_t*>(a.o) + off;
 #pragma unroll
-      for (int dt = 0; dt < DT; dt++)
+        for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 w = {o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv, o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv};
-          *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
-        }
+          for (int q4 = 0; q4 < 4; q4++) {
+            u32x2 h = {pack_bf16(o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv), pack_bf16(o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv)};
+            *reinterpret_cast<u32x2*>(op + dt * 32 + 8 * q4 + 4 * g) = h;
+          }
+      } else {
+        float* op = (to_final ? reinterpret_cast<float*>(a.o) : a.o_part) + off;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            f32x4 w = {o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv, o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv};
+            *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
+          }
+      }
       if (g == 0) {
         const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-        a.lse_part[(int64_t)(it.out_row[sub] + my_row) * a.n_q_heads + head] = lse;
+        (to_final ? a.lse : a.lse_part)[row * a.n_q_heads + head] = lse;
       }
     }
     __syncthreads();   // s_item is rewritten next
@@ -1244,28 +1260,46 @@ extern "C" int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int3
   return FCP_OK;
 }
 
-extern "C" int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                  float* o_part, float* lse_part, void* workspace, void* stream) {
+static int launch_fwd(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,
+                      float* o_part, float* lse_part, void* o, float* lse, void* workspace, void* stream) {
   int rc = validate_problem(p);
   if (rc) return rc;
   WsLayout L;
   rc = compute_layout(p, &L);
   if (rc) return rc;
   if (L.n_fwd_items == 0) return FCP_OK;
-  if (!q || !k || !v || !o_part || !lse_part || !workspace) { set_error("fcp_block_attn_fwd: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !workspace || (p->n_slot_rows && (!o_part || !lse_part))) { set_error("%s: NULL pointer", who); return FCP_ERR_INVALID_ARG; }
+  const bool direct = (p->flags & FCP_FLAG_DIRECT_SINGLE) != 0;
+  if (direct && (!o || !lse)) {
+    set_error("%s: FCP_FLAG_DIRECT_SINGLE needs the final o and lse (call fcp_block_attn_fwd_out)", who);
+    return FCP_ERR_INVALID_ARG;
+  }
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.o_part = o_part; a.lse_part = lse_part;
+  a.o = direct ? o : nullptr; a.lse = direct ? lse : nullptr;
+  a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
   a.hdr = reinterpret_cast<WsHeader*>(ws);
   a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);
   a.items = reinterpret_cast<const QItem*>(ws + L.off_fwd_items);
   a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.scale_log2 = resolve_scale(p) * kLog2e;
-  int grid = (int)std::min<int64_t>(L.n_fwd_items, (int64_t)cu_count() * kFwdWgPerCu);
+  const int grid = (int)std::min<int64_t>(L.n_fwd_items, (int64_t)cu_count() * kFwdWgPerCu);
   if (p->head_dim == 128) hipLaunchKernelGGL(fwd_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(fwd_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  return check_launch("fcp_block_attn_fwd");
+  return check_launch(who);
+}
+
+extern "C" int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                  float* o_part, float* lse_part, void* workspace, void* stream) {
+  return launch_fwd("fcp_block_attn_fwd", p, q, k, v, o_part, lse_part, nullptr, nullptr, workspace, stream);
+}
+
+extern "C" int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                      float* o_part, float* lse_part, void* o, float* lse,
+                                      void* workspace, void* stream) {
+  return launch_fwd("fcp_block_attn_fwd_out", p, q, k, v, o_part, lse_part, o, lse, workspace, stream);
 }
 
 extern "C" int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* lse_part,

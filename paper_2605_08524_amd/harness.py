@@ -46,7 +46,11 @@ class DevicePath:
             self.dv = torch.full((max(1, p.t_kv), Hkv, d), nan, **f32)
 
     def fwd(self):
-        B.fcp_block_attn_fwd(self.problem, self.q, self.k, self.v, self.o_part, self.lse_part, self.ws_ptr, self.stream)
+        if self.problem.flags & B.FCP_FLAG_DIRECT_SINGLE:
+            B.fcp_block_attn_fwd_out(self.problem, self.q, self.k, self.v, self.o_part, self.lse_part,
+                                     self.o, self.lse, self.ws_ptr, self.stream)
+        else:
+            B.fcp_block_attn_fwd(self.problem, self.q, self.k, self.v, self.o_part, self.lse_part, self.ws_ptr, self.stream)
 
     def merge(self):
         B.fcp_merge_partials(self.problem, self.o_part, self.lse_part, self.o, self.lse, self.ws_ptr, self.stream)

@@ -126,6 +126,30 @@ def test_config1_tiny(seed, coalesce):
     _full_parity(wl, backward=True, flags=F32)
 
 
+DIRECT = 2   # FCP_FLAG_DIRECT_SINGLE
+
+
+@pytest.mark.parametrize("case", range(len(EDGE)))
+@pytest.mark.parametrize("f32", [0, 1])
+def test_edge_cases_direct_single_slot(case, f32):
+    """With FCP_FLAG_DIRECT_SINGLE the forward writes query blocks that have one slot straight to
+    the final O / LSE and the merge handles only the others: same results as the oracle, and the
+    same bits as the two-step path for fp32 O."""
+    lens, bs, causal, c, hq, hkv, d, owned = EDGE[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=100 + case, name=f"edge{case}-direct")
+    res = _full_parity(wl, backward=bool(f32), flags=DIRECT | (F32 if f32 else 0), partials=False)
+    if f32:
+        two_step = run_path(wl, torch.device("cuda:0"), backward=False, flags=F32)
+        assert np.array_equal(res["o"], two_step["o"]) and np.array_equal(res["lse"], two_step["lse"])
+
+
+@pytest.mark.parametrize("coalesce", [0, 1])
+def test_config1_tiny_direct(coalesce):
+    wl = workloads.make_workload(1, 0)
+    wl.coalesce = coalesce
+    _full_parity(wl, backward=True, flags=DIRECT | F32, partials=False)
+
+
 def test_repeated_calls_reuse_the_workspace():
     """The queues' counters must be clean after every launch: run the path three times."""
     from paper_2605_08524_amd.harness import DevicePath
