@@ -340,7 +340,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // number of tiles of the item, and of iterations: tiles + 1 (pipeline fill), rounded up to even
+    // number of tiles of the item, and of iterations: tiles + 1 (pipeline fill)
     TileIter ti;                      // names the next tile to LOAD
     ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
     int n_it = 1;
@@ -349,7 +349,6 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       const int nc = pr.kind == FCP_KIND_DIAG ? min(pr.kv_len, ti.row_hi) : pr.kv_len;
       n_it += (nc + kFwdTileN - 1) / kFwdTileN;
     }
-    n_it = (n_it + 1) & ~1;
 
     // The load of one tile in two parts.  describe(): scalar bookkeeping with branches, run at
     // an iteration boundary.  issue(): branch-free, sits between the MFMAs.
@@ -502,7 +501,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     };
     for (int i = 0; i < n_it; i += 2) {
       iteration(s_a, s_b);
-      iteration(s_b, s_a);
+      if (i + 1 < n_it) iteration(s_b, s_a);
     }
     dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
 
@@ -561,6 +560,9 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
   const MergeItem it = a.items[blockIdx.x];
   const int sub = threadIdx.x / LPE, ln = threadIdx.x % LPE;
   for (int e0 = sub; e0 < it.n_rh; e0 += EPP * U) {
+    // One pass over the slots with a running maximum (the same recurrence as the online softmax):
+    // acc and tot are kept relative to mx and rescaled when a larger LSE arrives.  The loads of
+    // slot s+1 are in flight while slot s is folded in.
     float mx[U], tot[U];
     f32x4 acc[U];
     bool ok[U];
@@ -570,41 +572,41 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
       mx[u] = -INFINITY; tot[u] = 0.f;
       acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (it.n_slots > 1) {
-      for (int s = 0; s < it.n_slots; s++) {
-        const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
-#pragma unroll
-        for (int u = 0; u < U; u++)
-          if (ok[u]) mx[u] = fmaxf(mx[u], a.lse_part[base + u * EPP]);
-      }
-    }
-    for (int s = 0; s < it.n_slots; s++) {
+    float l[U], ln_[U];
+    f32x4 x[U], xn[U];
+    auto load = [&](int s, float (&ll)[U], f32x4 (&xx)[U]) {
       const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
-      float l[U];
-      f32x4 x[U];
 #pragma unroll
       for (int u = 0; u < U; u++) {
-        l[u] = -INFINITY;
-        x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        ll[u] = -INFINITY;
+        xx[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (ok[u]) {
-          l[u] = a.lse_part[base + u * EPP];
-          x[u] = *reinterpret_cast<const f32x4*>(a.o_part + (base + u * EPP) * D + ln * 4);
+          ll[u] = a.lse_part[base + u * EPP];
+          xx[u] = *reinterpret_cast<const f32x4*>(a.o_part + (base + u * EPP) * D + ln * 4);
+        }
+      }
+    };
+    if (it.n_slots > 0) load(0, l, x);
+    for (int s = 0; s < it.n_slots; s++) {
+      if (s + 1 < it.n_slots) load(s + 1, ln_, xn);
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        // an empty partial (LSE = -inf) carries weight 0; its payload must not leak through (0 * NaN)
+        if (l[u] != -INFINITY) {
+          const float m_new = fmaxf(mx[u], l[u]);
+          const float keep = __expf(mx[u] - m_new);        // mx = -inf -> 0
+          const float w = __expf(l[u] - m_new);
+          tot[u] = tot[u] * keep + w;
+          acc[u] = acc[u] * keep + w * x[u];
+          mx[u] = m_new;
         }
       }
 #pragma unroll
-      for (int u = 0; u < U; u++) {
-        if (it.n_slots == 1) mx[u] = l[u];                       // a single partial is its own maximum
-        const float m_use = (mx[u] == -INFINITY) ? 0.f : mx[u];
-        const float w = __expf(l[u] - m_use);
-        tot[u] += w;
-        // an empty partial carries weight 0; its payload must not leak through (0 * NaN)
-        if (w > 0.f) acc[u] += w * x[u];
-      }
+      for (int u = 0; u < U; u++) { l[u] = ln_[u]; x[u] = xn[u]; }
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
       if (!ok[u]) continue;
-      const float m_use = (mx[u] == -INFINITY) ? 0.f : mx[u];
       const float inv = tot[u] > 0.f ? 1.0f / tot[u] : 0.f;
       const f32x4 r = acc[u] * inv;
       const int64_t out = (int64_t)it.out_rh + e0 + u * EPP;
@@ -614,7 +616,7 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
         u32x2 h = {pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3])};
         *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.o) + out * D + ln * 4) = h;
       }
-      if (ln == 0) a.lse[out] = tot[u] > 0.f ? m_use + __logf(tot[u]) : -INFINITY;
+      if (ln == 0) a.lse[out] = tot[u] > 0.f ? mx[u] + __logf(tot[u]) : -INFINITY;
     }
   }
 }
