@@ -499,10 +499,11 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         b_v = (b_v == NB - 1) ? 0 : b_v + 1;
       }
     };
-    for (int i = 0; i < n_it; i += 2) {
+    for (int i = 0; i + 1 < n_it; i += 2) {
       iteration(s_a, s_b);
-      if (i + 1 < n_it) iteration(s_b, s_a);
+      iteration(s_b, s_a);
     }
+    if (n_it & 1) iteration(s_a, s_b);     // a tail, not a branch inside the loop (which costs dozens of spills)
     dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
 
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
