@@ -121,7 +121,11 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   for (int b = 0; b < p->n_q_blocks; b++) {
     if (!(direct && slots_of[b] == 1))
       L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
-    L->n_dq_items += ceil_div(p->q_blocks[b].tok_len, kFwdTileM) * p->n_q_heads;
+    {
+      const int G = p->n_q_heads / p->n_kv_heads;
+      const int64_t n_tiles = ceil_div(p->q_blocks[b].tok_len, kFwdTileM);
+      L->n_dq_items += (G % 2 == 0) ? n_tiles * (p->n_q_heads / 2) : ceil_div(n_tiles, 2) * p->n_q_heads;
+    }
     L->t_q += p->q_blocks[b].tok_len;
   }
   for (int b = 0; b < p->n_kv_blocks; b++) L->t_kv += p->kv_blocks[b].tok_len;
@@ -137,7 +141,7 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   L->off_bwd_items = off;   off = align(off + sizeof(BwdItem) * (size_t)std::max<int64_t>(1, L->n_bwd_items));
   L->off_merge_items = off; off = align(off + sizeof(MergeItem) * (size_t)std::max<int64_t>(1, L->n_merge_items));
   L->off_slot_rh = off;     off = align(off + sizeof(int32_t) * (size_t)std::max(1, p->n_slots));
-  L->off_dq_items = off;    off = align(off + sizeof(FwdItem) * (size_t)std::max<int64_t>(1, L->n_dq_items));
+  L->off_dq_items = off;    off = align(off + sizeof(QItem) * (size_t)std::max<int64_t>(1, L->n_dq_items));
   // backward scratch, head-major [Hq][T_q] fp32: D * scale, then LSE * log2(e)
   L->off_dls = off;         off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
   L->off_lse2 = off;        off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
@@ -428,7 +432,8 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     if (!flat.empty()) std::memcpy(host.data() + L.off_bwd_items, flat.data(), flat.size() * sizeof(BwdItem));
   }
   // ---- backward dQ: query-stationary items over ALL pairs of a query block (its slots are
-  // consecutive, so their pairs form one range); one group per (query block, KV head).
+  // consecutive, so their pairs form one range); one group per (query block, KV head); items
+  // join two sub-tiles like the forward's.
   {
     std::vector<int32_t> pb(p->n_q_blocks, 0), pn(p->n_q_blocks, 0);
     for (int s = 0; s < p->n_slots; s++) {
@@ -436,7 +441,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
       if (pn[sl.q_blk] == 0) pb[sl.q_blk] = sl.pair_begin;
       pn[sl.q_blk] += sl.n_pairs;
     }
-    std::vector<std::vector<FwdItem>> groups;
+    std::vector<std::vector<QItem>> groups;
     std::vector<int64_t> weight;
     groups.reserve((size_t)p->n_q_blocks * p->n_kv_heads);
     for (int b = 0; b < p->n_q_blocks; b++) {
@@ -451,25 +456,43 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
           tile_w[t] += (int64_t)rows * cols;
         }
       }
+      auto sub = [&](QItem* it, int k, int t, int head) {
+        const int off = t * kFwdTileM;
+        it->q_start[k] = qb.tok_start + off; it->q_rows[k] = std::min(kFwdTileM, qb.tok_len - off);
+        it->out_row[k] = qb.tok_start + off; it->tile_off[k] = off; it->head[k] = head;
+      };
       for (int g = 0; g < p->n_kv_heads; g++) {
-        std::vector<FwdItem> items;
+        std::vector<QItem> items;
         int64_t w = 0;
-        for (int t = n_tiles - 1; t >= 0; t--) {
-          const int off = t * kFwdTileM;
-          const int rows = std::min(kFwdTileM, qb.tok_len - off);
-          for (int hh = 0; hh < G; hh++) {
-            items.push_back({qb.tok_start + off, rows, qb.tok_start + off, off, pb[b], pn[b], g * G + hh, 0});
-            w += tile_w[t];
-          }
+        if (G % 2 == 0) {
+          for (int t = n_tiles - 1; t >= 0; t--)
+            for (int hh = 0; hh < G; hh += 2) {
+              QItem it{};
+              it.pair_begin = pb[b]; it.n_pairs = pn[b];
+              sub(&it, 0, t, g * G + hh); sub(&it, 1, t, g * G + hh + 1);
+              items.push_back(it);
+              w += 2 * tile_w[t];
+            }
+        } else {
+          for (int t = n_tiles - 1; t >= 0; t -= 2)
+            for (int hh = 0; hh < G; hh++) {
+              QItem it{};
+              it.pair_begin = pb[b]; it.n_pairs = pn[b];
+              sub(&it, 0, t, g * G + hh);
+              if (t >= 1) { sub(&it, 1, t - 1, g * G + hh); w += tile_w[t - 1]; }
+              else { it.q_start[1] = it.q_start[0]; it.q_rows[1] = 0; it.out_row[1] = it.out_row[0]; it.tile_off[1] = it.tile_off[0]; it.head[1] = it.head[0]; }
+              items.push_back(it);
+              w += tile_w[t];
+            }
         }
         groups.push_back(std::move(items));
         weight.push_back(w);
       }
     }
-    std::vector<FwdItem> flat;
+    std::vector<QItem> flat;
     spread_over_xcds(groups, weight, &flat, hdr->dq_begin);
     if ((int64_t)flat.size() != L.n_dq_items) { set_error("internal: dQ item count mismatch"); return FCP_ERR_INVALID_ARG; }
-    if (!flat.empty()) std::memcpy(host.data() + L.off_dq_items, flat.data(), flat.size() * sizeof(FwdItem));
+    if (!flat.empty()) std::memcpy(host.data() + L.off_dq_items, flat.data(), flat.size() * sizeof(QItem));
   }
   // ---- merge: row-head chunks per query block; slots of a query block are consecutive.
   {

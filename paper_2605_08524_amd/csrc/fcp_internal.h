@@ -16,9 +16,9 @@ constexpr int kMergeChunk = 1024;   // (row, head) entries per merge work item
 
 // Device-side records (all int32 so the host can build them as plain arrays).
 struct DevPair { int32_t kv_start, kv_len, kind, pad; };
-struct FwdItem { int32_t q_start, q_rows, out_row, tile_off, pair_begin, n_pairs, head, pad; };
 // Query-stationary item of two 128-row sub-tiles that walk the same pair list and share a KV head
 // (two query heads of a group, or two neighbouring row tiles of one head; q_rows[1] = 0: none).
+// pad[0] != 0 (forward items only): the slot is the only one of its query block.
 struct QItem { int32_t q_start[2], q_rows[2], out_row[2], tile_off[2], head[2], pair_begin, n_pairs, pad[4]; };
 struct BwdDep  { int32_t q_start, q_len, kind, pad; };
 struct BwdItem { int32_t kv_start, kv_rows, tile_off, dep_begin, n_deps, kv_head, pad0, pad1; };

@@ -722,7 +722,7 @@ struct BwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse2; const float* dls;     // head-major [Hq][T_q]: LSE*log2(e) (+inf for empty rows), D*scale
   float* dq; float* dk; float* dv;
-  WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const FwdItem* dq_items;
+  WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
   int64_t t_q;
   int32_t n_q_heads, n_kv_heads;
   float scale, scale_log2;
@@ -1061,8 +1061,9 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 }
 
 // =====================================================================================
-// Backward, part 2 -- dQ.  Query-stationary like the forward: item = (query block, 128-row
-// tile, query head) over all pairs of the block; lane = query row.
+// Backward, part 2 -- dQ.  Query-stationary like the forward and with the same item shape (two
+// 128-row query sub-tiles that share a KV head, here over all pairs of the query block); 8 waves
+// share one double-buffered stream of [K | V] tiles; lane = query row.
 //   S^T = K Q^T, dP^T = V dO^T       (A = K / V rows from LDS, B = Q / dO fragments in registers)
 //   P^T = exp2(S^T*c - LSE*log2e), dS^T = P^T o (dP^T - D) * scale     (LSE, D per lane)
 //   dQ^T += K^T dS^T                 (A = K by transpose reads, B = accumulator registers)
@@ -1070,7 +1071,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 // diagonal needs a mask.  Every dQ row has one writer: plain stores, deterministic.
 // =====================================================================================
 template <int D>
-__global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
+__global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
   constexpr int TB = tile_bytes<D>(kFwdTileN);
@@ -1079,6 +1080,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+  const int sub = wave >> 2, wq = wave & 3;                    // sub-item, 32-row group inside it
   const int l32 = lane & 31, g = lane >> 5;
   const int group = a.n_q_heads / a.n_kv_heads;
   const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
@@ -1110,18 +1112,19 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
     __syncthreads();
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
-    const FwdItem it = a.dq_items[item_idx];
-    const int kvh = it.head / group;
-    const int my_row = wave * 32 + l32;
-    const bool row_ok = my_row < it.q_rows;
-    const int wave_row_lo = it.tile_off + wave * 32;
+    const QItem it = a.dq_items[item_idx];
+    const int q_start = it.q_start[sub], q_rows = it.q_rows[sub], tile_off_q = it.tile_off[sub], head = it.head[sub];
+    const int kvh = it.head[0] / group;
+    const int my_row = wq * 32 + l32;
+    const bool row_ok = my_row < q_rows;
+    const int wave_row_lo = tile_off_q + wq * 32;
     const uint16_t* kbase = a.k + (int64_t)kvh * D;
     const uint16_t* vbase = a.v + (int64_t)kvh * D;
 
     bf16x8 qf[KC], dof[KC];
     float lse_l = INFINITY, dl_l = 0.f;     // rows past the end: P = exp2(-inf) = 0
     {
-      const int64_t off = (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D + 8 * g;
+      const int64_t off = (int64_t)(q_start + my_row) * q_row_stride + (int64_t)head * D + 8 * g;
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) {
         u32x4 zq = {0, 0, 0, 0}, zd = {0, 0, 0, 0};
@@ -1132,7 +1135,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
         qf[kc] = as_bf16x8(zq); dof[kc] = as_bf16x8(zd);
       }
       if (row_ok) {
-        const int64_t hr = (int64_t)it.head * a.t_q + it.q_start + my_row;
+        const int64_t hr = (int64_t)head * a.t_q + q_start + my_row;
         lse_l = a.lse2[hr];
         dl_l = a.dls[hr];
       }
@@ -1144,11 +1147,11 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
       for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
 
     TileIter ti;
-    ti.init(a.pairs, it.pair_begin, it.n_pairs, it.tile_off + it.q_rows);
+    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
     auto dma = [&](int b) {
       const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
-      tile_dma<D, kFwdTileN, 4>(lds_kv[b], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
-      tile_dma<D, kFwdTileN, 4>(lds_kv[b] + TB, vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      tile_dma<D, kFwdTileN, 8>(lds_kv[b], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      tile_dma<D, kFwdTileN, 8>(lds_kv[b] + TB, vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
     };
     DevPair tp = ti.cur;
     int tc0 = 0;
@@ -1165,7 +1168,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
       const bool diag = tp.kind == FCP_KIND_DIAG;
       if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
         const bool need_mask = diag && tc0 + kFwdTileN - 1 > wave_row_lo;
-        const int limit = it.tile_off + my_row;      // last visible column of a DIAG pair
+        const int limit = tile_off_q + my_row;      // last visible column of a DIAG pair
         // the two 32-row halves of the KV tile one after the other: half the live accumulators
 #pragma unroll
         for (int rt = 0; rt < 2; rt++) {
@@ -1208,7 +1211,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(BwdArgs a) {
       switch_buffer();
     }
     if (row_ok) {
-      float* op = a.dq + (int64_t)(it.q_start + my_row) * q_row_stride + (int64_t)it.head * D;
+      float* op = a.dq + (int64_t)(q_start + my_row) * q_row_stride + (int64_t)head * D;
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -1249,7 +1252,7 @@ static float resolve_scale(const fcp_problem* p) {
 
 constexpr int kFwdWgPerCu = 1;   // 8 waves, two per SIMD
 constexpr int kDkdvWgPerCu = 1;   // 8 waves, two per SIMD
-constexpr int kDqWgPerCu = 2;
+constexpr int kDqWgPerCu = 1;   // 8 waves, two per SIMD
 
 }  // namespace fcp
 
@@ -1359,7 +1362,7 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
   a->pairs = reinterpret_cast<const DevPair*>(ws + L->off_pairs);
   a->deps = reinterpret_cast<const BwdDep*>(ws + L->off_bwd_deps);
   a->items = reinterpret_cast<const BwdItem*>(ws + L->off_bwd_items);
-  a->dq_items = reinterpret_cast<const FwdItem*>(ws + L->off_dq_items);
+  a->dq_items = reinterpret_cast<const QItem*>(ws + L->off_dq_items);
   a->n_q_heads = p->n_q_heads; a->n_kv_heads = p->n_kv_heads;
   a->scale = resolve_scale(p); a->scale_log2 = a->scale * kLog2e;
   a->dq = nullptr; a->dk = nullptr; a->dv = nullptr;
@@ -1393,8 +1396,8 @@ extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const 
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dq = dq;
   const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+  if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch("fcp_block_attn_bwd_dq");
 }
 
