@@ -80,6 +80,47 @@ def cpu_baseline(wl, budget_s=20.0):
     }
 
 
+def sweep(args):
+    """Throughput of the training step against block size and coalesce degree at fixed tokens: the
+    paper's block-size study (its single-GPU attention efficiency collapses below 2K-token blocks
+    and saturates above 4K; its system picks 4K blocks, coalesce degree 16) redone for this path,
+    where one persistent launch covers all slots.  One JSON line per point."""
+    import torch
+    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, workloads
+    from paper_2605_08524_amd.harness import DevicePath
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream(dev)
+    wl = workloads.make_workload(5, args.seed)
+    for bs in (256, 512, 1024, 2048, 4096, 8192):
+        for c in (1, 4, 16, 0):
+            wl.block_size, wl.coalesce = bs, c
+            dp = DevicePath(wl, dev, flags=FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_O_F32, backward=True, stream=stream)
+            f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
+            stages = [dp.fwd, dp.merge, dp.bwd_pre, dp.bwd_dkdv, dp.bwd_dq]
+            for _ in range(args.warmup):
+                for fn in stages:
+                    fn()
+            torch.cuda.synchronize(dev)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
+            for s_ in range(args.steps):
+                for i, fn in enumerate(stages):
+                    evs[s_][i].record(stream)
+                    fn()
+                evs[s_][len(stages)].record(stream)
+            torch.cuda.synchronize(dev)
+            ms = [sum(evs[s_][i].elapsed_time(evs[s_][i + 1]) for s_ in range(args.steps)) / args.steps for i in range(len(stages))]
+            step_ms = sum(ms)
+            print(json.dumps({
+                "block_size": bs, "coalesce": c, "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
+                "nnz_per_head": nnz, "ms": {k: round(v, 3) for k, v in zip(("fwd", "merge", "bwd_pre", "bwd_dkdv", "bwd_dq"), ms)},
+                "ms_per_step": round(step_ms, 3), "tflops": round((f_fwd + f_bwd) / step_ms / 1e9, 1),
+                "fwd_tflops": round(f_fwd / (ms[0] + ms[1]) / 1e9, 1)}), flush=True)
+            del dp
+            torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,11 +134,16 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
+    ap.add_argument("--sweep", action="store_true",
+                    help="block size x coalesce degree sweep of the training step (one JSON line per point) instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    if args.sweep:
+        sweep(args)
+        return
     import torch
     from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, fcp_device_info, workloads
     from paper_2605_08524_amd.harness import DevicePath
