@@ -399,9 +399,13 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       u32x4 pb[4];                    // P^T of tile i as four B operands (rt, j)
       float rs = 0.f;
       float p_prev = 0.f;
+      // the exponential of the NEXT element is issued before this one is consumed, so its latency
+      // does not sit in a dependent chain (the wave issues in order)
+      float p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][0], a.scale_log2, -m_use));
       auto expo = [&](int e) {        // element e = (rt, r) of tile i
-        const int rt = e >> 4, r = e & 15;
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[rt][r], a.scale_log2, -m_use));
+        const int r = e & 15;
+        const float p = p_ahead;
+        if (e + 1 < 32) p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[(e + 1) >> 4][(e + 1) & 15], a.scale_log2, -m_use));
         rs += p;
         if (r & 1) {
           pb[e >> 3][(e >> 1) & 3] = pack_bf16(p_prev, p);
@@ -456,7 +460,11 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       // end of the item), then its maximum
       {
         const TileMeta tm = meta[0];
-        if (tm.len == 0 || tm.c0 + kFwdTileN > tm.len || (tm.diag && tm.c0 + kFwdTileN - 1 > wave_row_lo)) {
+        // readfirstlane: the condition is wave-uniform, but the compiler does not know it and would
+        // otherwise run the rare path on every tile as 64 compares and selects
+        const int need_mask = __builtin_amdgcn_readfirstlane(
+            (int)(tm.len == 0 || tm.c0 + kFwdTileN > tm.len || (tm.diag && tm.c0 + kFwdTileN - 1 > wave_row_lo)));
+        if (need_mask) {
           // last visible column for this lane, relative to the tile's first column
           const int limit = (tm.diag ? min(tm.len - 1, my_limit) : tm.len - 1) - tm.c0 - 4 * g;
 #pragma unroll
@@ -985,6 +993,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         uint32_t pk[16];           // [0..7] P pairs, [8..15] dS pairs: four B operands for the consumer
         float p_prev = 0.f, ds_prev = 0.f;
         const uint32_t hdst = lds_h0 + (hb ^ 1) * (4 * 4096);
+        float p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0], a.scale_log2, -lse_c[0]));
 #pragma unroll
         for (int k = 0; k < NS; k++) {
           const int kc = k / 2;
@@ -1021,8 +1030,14 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
                 dl_n = __builtin_bit_cast(f32x4, lds_read16(sc_a + 32 * ((r >> 2) + 1) + 128));
               }
             }
-            const float lse_r = lse_c[r & 3], dl_r = dl_c[r & 3];
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], a.scale_log2, -lse_r));
+            // the exponential of the NEXT register is issued before this register is finished, so
+            // its latency does not sit in a dependent chain (the wave issues in order)
+            float p = p_ahead;
+            if (r + 1 < 16) {
+              const float lse_q = ((r + 1) & 3) ? lse_c[(r + 1) & 3] : lse_n[0];
+              p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r + 1], a.scale_log2, -lse_q));
+            }
+            const float dl_r = dl_c[r & 3];
             if constexpr (MASK) p = (kvg > thr_s + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
             const float ds = p * __builtin_fmaf(dpc[r], a.scale, -dl_r);
             if (r & 1) {
