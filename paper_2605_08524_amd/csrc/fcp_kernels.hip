@@ -866,18 +866,28 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       uint32_t d_lim = 0;                  // byte offset of the last valid row
       int d_valid = 0;
       int64_t d_sc = 0;                    // element offset of the step's first row in the head-major scalars
+      const uint32_t row_bytes = (uint32_t)(q_row_stride * 2);
+      int run_dep = -1, run_hh = -1;       // the run (dependency, head) of the step described last
       auto describe = [&]() {
-        d_q = reinterpret_cast<uint64_t>(zeros); d_do = d_q; d_lim = 0; d_valid = 0; d_sc = 0;
-        if (si.more) {
+        if (!si.more) {
+          d_q = reinterpret_cast<uint64_t>(zeros); d_do = d_q; d_lim = 0; d_valid = 0; d_sc = 0;
+          run_dep = -1;
+          return;
+        }
+        if (si.dep == run_dep && si.hh == run_hh) {
+          // the next 32 rows of the same run: advance the pointers instead of recomputing them
+          d_q += 32 * (uint64_t)row_bytes; d_do += 32 * (uint64_t)row_bytes; d_sc += 32;
+        } else {
           const int head = it.kv_head * group + si.hh;
           const int64_t row = (int64_t)(si.cur.q_start + si.q0);
           d_q = reinterpret_cast<uint64_t>(a.q + row * q_row_stride + (int64_t)head * D);
           d_do = reinterpret_cast<uint64_t>(a.d_o + row * q_row_stride + (int64_t)head * D);
-          d_valid = min(32, si.cur.q_len - si.q0);
-          d_lim = (uint32_t)((d_valid - 1) * q_row_stride * 2);
           d_sc = (int64_t)head * a.t_q + row;
-          si.advance();
+          run_dep = si.dep; run_hh = si.hh;
         }
+        d_valid = min(32, si.cur.q_len - si.q0);
+        d_lim = (uint32_t)(d_valid - 1) * row_bytes;
+        si.advance();
       };
       auto issue = [&]() {
         const uint32_t lbase = lds_addr(lds_t[0]) + b_dma * BUF;
@@ -933,7 +943,11 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         }
         // the tiles of step i+4 have landed once at most two steps' loads are in flight
         __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * DMA_PER_STEP) & 15) | (((2 * DMA_PER_STEP) >> 4) << 14));
-        __syncthreads();
+        // A bare barrier: __syncthreads() would first wait for every LDS operation of this wave,
+        // i.e. for the operands of the next interval that were just requested (about 200 cycles on
+        // the wave that already is the slower one).  Nothing this wave wrote needs publishing: its
+        // DMA loads have landed (vmcnt above), and the operands it read have been consumed by MFMAs.
+        asm volatile("s_barrier" ::: "memory");
         describe();
         hb ^= 1;
       }
@@ -1431,3 +1445,4 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
   if (rc) return rc;
   return fcp_block_attn_bwd_dq(p, q, k, v, d_o, dq, workspace, stream);
 }
+
