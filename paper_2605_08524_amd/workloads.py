@@ -189,3 +189,27 @@ def custom_workload(seq_lens, block_size, causal=1, coalesce=0, n_q_heads=4, n_k
     return Workload(name, seed, np.asarray(seq_lens, dtype=np.int32), int(block_size), int(causal),
                     int(coalesce), int(n_q_heads), int(n_kv_heads), int(head_dim),
                     q_owned=None if q_owned is None else np.asarray(q_owned, dtype=np.int32).reshape(-1, 2))
+
+
+def length_trace(kind: str, total_tokens: int, seed: int = 0) -> np.ndarray:
+    """Sequence lengths of one global batch for the scheduling experiments (paper, appendix
+    "Synthetic Workloads"): lognormal lengths clipped to [1K, 512K], drawn until `total_tokens`
+    is reached (the last one truncated).
+      "lognormal": sigma 0.7, mean length 16K (the less long-tailed trace);
+      "bimodal"  : each length from sigma 0.5 / mean 16K or sigma 0.5 / mean 64K with equal odds.
+    The mean of a lognormal is exp(mu + sigma^2 / 2), which fixes mu."""
+    rng = np.random.default_rng([int(seed), 7])
+    out, acc = [], 0
+    while acc < total_tokens:
+        if kind == "lognormal":
+            sigma, mean = 0.7, 16384.0
+        elif kind == "bimodal":
+            sigma, mean = 0.5, (16384.0 if rng.random() < 0.5 else 65536.0)
+        else:
+            raise ValueError(f"unknown trace kind {kind}")
+        mu = np.log(mean) - 0.5 * sigma * sigma
+        L = int(np.clip(np.rint(np.exp(rng.normal(mu, sigma))), 1024, 524288))
+        L = min(L, total_tokens - acc)
+        out.append(L)
+        acc += L
+    return np.asarray(out, dtype=np.int32)
