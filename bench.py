@@ -121,6 +121,91 @@ def sweep(args):
             torch.cuda.empty_cache()
 
 
+def distribute(args):
+    """Block distributor and congestion-free solver on the appendix's synthetic length traces: for each
+    trace and worker count, the host time of the whole chain (block costs, greedy load-balanced
+    assignment, data-flow edges, Delta sub-stages), the compute / memory / communication imbalance ratios
+    ((max - mean) / max, as in the paper's balance study) and the oracle's time for the same steps where it
+    finishes in seconds.  With a GPU, the most loaded worker's share of the 8-worker lognormal batch is
+    then run forward + backward at its real shape.  One JSON line per point."""
+    import numpy as np
+    import paper_2605_08524_amd as fcp
+    from oracle import fcp_sched_oracle as sch
+    from paper_2605_08524_amd import workloads
+
+    def ratio(x):
+        x = np.asarray(x, dtype=np.float64)
+        return round(float((x.max() - x.mean()) / x.max()), 4) if x.max() > 0 else 0.0
+
+    bs, per_worker = 4096, 131072
+    for kind in ("lognormal", "bimodal"):
+        for n in (8, 32, 64, 128, 256):
+            lens = workloads.length_trace(kind, n * per_worker, args.seed)
+            t = [time.perf_counter()]
+            blocks, mem, comp = fcp.fcp_block_costs(lens, bs, 1)
+            t.append(time.perf_counter())
+            owner, w_m, w_c = fcp.fcp_assign_blocks(mem, comp, n)
+            t.append(time.perf_counter())
+            edges = fcp.fcp_comm_edges(blocks, owner, n, 1)
+            t.append(time.perf_counter())
+            delta = fcp.fcp_solve_matchings(edges, n)
+            t.append(time.perf_counter())
+            stage, n_stages = fcp.fcp_coalesce_stages(edges, 16)
+            t.append(time.perf_counter())
+            line = {
+                "trace": kind, "n_workers": n, "n_seqs": int(len(lens)), "n_blocks": int(len(blocks)), "block_size": bs,
+                "imbalance": {"compute": ratio(w_c), "memory": ratio(w_m),
+                              "send": ratio(np.bincount(edges[:, 0], minlength=n)), "recv": ratio(np.bincount(edges[:, 1], minlength=n))},
+                "n_edges": int(len(edges)), "delta": int(delta), "stages_c16": int(n_stages),
+                "host_ms": {k: round((b - a) * 1e3, 3) for k, a, b in zip(("costs", "assign", "edges", "solve", "coalesce"), t, t[1:])},
+            }
+            if n <= 64:       # the oracle's solver is the slow one: bounded to the sizes it finishes in seconds
+                t0 = time.perf_counter()
+                ob, om, oc = sch.block_costs(lens, bs, 1)
+                o_owner, _, _ = sch.assign_blocks(om, oc, n)
+                t1 = time.perf_counter()
+                o_edges = sch.comm_edges(ob, o_owner, 1)
+                o_stage, o_delta = sch.solve_matchings([e[0] for e in o_edges], [e[1] for e in o_edges], n)
+                t2 = time.perf_counter()
+                assert o_owner == owner.tolist() and o_delta == delta
+                line["oracle_ms"] = {"costs+assign": round((t1 - t0) * 1e3, 1), "edges+solve": round((t2 - t1) * 1e3, 1)}
+            print(json.dumps(line), flush=True)
+
+    import torch
+    if not torch.cuda.is_available():
+        return
+    from paper_2605_08524_amd.harness import DevicePath
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream(dev)
+    n = 8
+    lens = workloads.length_trace("lognormal", n * per_worker, args.seed)
+    blocks, mem, comp = fcp.fcp_block_costs(lens, bs, 1)
+    owner, w_m, w_c = fcp.fcp_assign_blocks(mem, comp, n)
+    heavy = int(np.argmax(w_c))
+    wl = workloads.custom_workload(lens, bs, causal=1, coalesce=16, n_q_heads=32, n_kv_heads=8, head_dim=128,
+                                   q_owned=fcp.fcp_worker_blocks(blocks, owner, heavy), seed=args.seed, name="heaviest-share")
+    dp = DevicePath(wl, dev, flags=fcp.FCP_FLAG_DIRECT_SINGLE | fcp.FCP_FLAG_O_F32, backward=True, stream=stream)
+    f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
+    assert nnz == int(w_c[heavy])
+    stages = [dp.fwd, dp.merge, dp.bwd_pre, dp.bwd_dkdv, dp.bwd_dq]
+    for _ in range(args.warmup):
+        for fn in stages:
+            fn()
+    torch.cuda.synchronize(dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        for fn in stages:
+            fn()
+    e1.record(stream)
+    torch.cuda.synchronize(dev)
+    ms = e0.elapsed_time(e1) / args.steps
+    print(json.dumps({"share_of_worker": heavy, "n_workers": n, "trace": "lognormal", "tokens_q": int(w_m[heavy]),
+                      "tokens_kv_resident": int(lens.sum()), "nnz_per_head": nnz, "n_pairs": int(len(dp.plan["pairs"])),
+                      "ms_per_step": round(ms, 3), "tflops": round((f_fwd + f_bwd) / ms / 1e9, 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,6 +221,9 @@ def main():
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
     ap.add_argument("--sweep", action="store_true",
                     help="block size x coalesce degree sweep of the training step (one JSON line per point) instead of the benchmark line")
+    ap.add_argument("--distribute", action="store_true",
+                    help="block distributor + congestion-free solver study on synthetic length traces (host timings, "
+                         "imbalance ratios; the most loaded worker's share on the GPU if there is one) instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -143,6 +231,9 @@ def main():
 
     if args.sweep:
         sweep(args)
+        return
+    if args.distribute:
+        distribute(args)
         return
     import torch
     from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, fcp_device_info, workloads

@@ -40,7 +40,8 @@ typedef enum {
   FCP_ERR_INVALID_ARG = -1,      /* null pointer, negative size, owned block out of range ... */
   FCP_ERR_BUFFER_TOO_SMALL = -2, /* a table capacity (or the workspace) is too small; needed counts are written back */
   FCP_ERR_UNSUPPORTED = -3,      /* head_dim not in {64,128}, Hq % Hkv != 0, ... */
-  FCP_ERR_HIP = -4               /* a HIP call failed; see fcp_last_error() */
+  FCP_ERR_HIP = -4,              /* a HIP call failed; see fcp_last_error() */
+  FCP_ERR_INFEASIBLE = -5        /* the scheduling problem has no solution under the given limits */
 } fcp_status;
 
 enum { FCP_KIND_FULL = 0, FCP_KIND_DIAG = 1 };

@@ -21,6 +21,7 @@ FCP_ERR_INVALID_ARG = -1
 FCP_ERR_BUFFER_TOO_SMALL = -2
 FCP_ERR_UNSUPPORTED = -3
 FCP_ERR_HIP = -4
+FCP_ERR_INFEASIBLE = -5
 FCP_KIND_FULL, FCP_KIND_DIAG = 0, 1
 FCP_FLAG_O_F32 = 1
 FCP_FLAG_DIRECT_SINGLE = 2
@@ -29,6 +30,8 @@ EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_last_error", "fcp_device_info",
+    "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
+    "fcp_coalesce_stages",
 )
 
 
@@ -53,6 +56,13 @@ def _load():
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
             "There is no CPU fallback.")
+    # PyTorch ships a HIP runtime of its own.  Whichever copy is loaded first serves the whole process
+    # (same SONAME), and tensors made by torch are only usable by this library if both talk to one
+    # runtime: load torch's first when torch is installed.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     i32p = C.POINTER(C.c_int32)
     lib.fcp_plan_blocks.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32,
@@ -66,6 +76,14 @@ def _load():
     lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
     lib.fcp_block_attn_bwd_dkdv.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 8
     lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
+    i64p = C.POINTER(C.c_int64)
+    lib.fcp_block_costs.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, i32p]
+    lib.fcp_assign_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int64,
+                                      C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fcp_worker_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, i32p]
+    lib.fcp_comm_edges.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, i64p]
+    lib.fcp_solve_matchings.argtypes = [C.c_void_p, C.c_int64, C.c_int32, i32p]
+    lib.fcp_coalesce_stages.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, i32p]
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
     for name in EXPORTS:
@@ -199,3 +217,77 @@ def fcp_device_info():
     a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
     _check(_lib.fcp_device_info(C.byref(a), C.byref(b), C.byref(c)))
     return dict(n_compute_units=a.value, fwd_grid=b.value, bwd_grid=c.value)
+
+
+# ---------------------------------------------------------------- host-side scheduling (fcp_sched.h)
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def fcp_block_costs(seq_lens, block_size, causal=1):
+    """Returns (blocks int32 [n,4], mem int64 [n], comp int64 [n])."""
+    sl = _i32(np.asarray(seq_lens).reshape(-1))
+    i32p = C.POINTER(C.c_int32)
+    n = C.c_int32(0)
+    _check(_lib.fcp_block_costs(sl.ctypes.data_as(i32p), len(sl), int(block_size), int(causal), None, None, None, C.byref(n)))
+    blocks = np.zeros((max(1, n.value), 4), dtype=np.int32)
+    mem = np.zeros(max(1, n.value), dtype=np.int64)
+    comp = np.zeros(max(1, n.value), dtype=np.int64)
+    _check(_lib.fcp_block_costs(sl.ctypes.data_as(i32p), len(sl), int(block_size), int(causal),
+                                blocks.ctypes.data, mem.ctypes.data, comp.ctypes.data, C.byref(n)))
+    return blocks[: n.value], mem[: n.value], comp[: n.value]
+
+
+def fcp_assign_blocks(mem, comp, n_workers, alpha=1.0, beta=1.0, mem_limit=0, delta=0.0):
+    """Returns (owner int32 [n], worker_mem int64 [N], worker_comp int64 [N])."""
+    mem, comp = _i64(mem), _i64(comp)
+    if mem.shape != comp.shape:
+        raise ValueError("mem and comp differ in length")
+    owner = np.full(max(1, len(mem)), -1, dtype=np.int32)
+    w_m = np.zeros(max(1, int(n_workers)), dtype=np.int64)
+    w_c = np.zeros(max(1, int(n_workers)), dtype=np.int64)
+    _check(_lib.fcp_assign_blocks(mem.ctypes.data, comp.ctypes.data, len(mem), int(n_workers), float(alpha), float(beta),
+                                  int(mem_limit), float(delta), owner.ctypes.data, w_m.ctypes.data, w_c.ctypes.data))
+    return owner[: len(mem)], w_m[: max(0, int(n_workers))], w_c[: max(0, int(n_workers))]
+
+
+def fcp_worker_blocks(blocks, owner, worker):
+    """Returns the worker's q_owned table, int32 [n,2] of (seq, idx)."""
+    blocks, owner = _i32(np.asarray(blocks).reshape(-1, 4)), _i32(owner)
+    n = C.c_int32(0)
+    _check(_lib.fcp_worker_blocks(blocks.ctypes.data, owner.ctypes.data, len(owner), int(worker), None, C.byref(n)))
+    out = np.zeros((max(1, n.value), 2), dtype=np.int32)
+    _check(_lib.fcp_worker_blocks(blocks.ctypes.data, owner.ctypes.data, len(owner), int(worker), out.ctypes.data, C.byref(n)))
+    return out[: n.value]
+
+
+def fcp_comm_edges(blocks, owner, n_workers, causal=1):
+    """Returns edges int32 [E,4] of (src, dst, kv_blk, stage = -1)."""
+    blocks, owner = _i32(np.asarray(blocks).reshape(-1, 4)), _i32(owner)
+    n = C.c_int64(0)
+    _check(_lib.fcp_comm_edges(blocks.ctypes.data, owner.ctypes.data, len(owner), int(n_workers), int(causal), None, C.byref(n)))
+    edges = np.zeros((max(1, n.value), 4), dtype=np.int32)
+    _check(_lib.fcp_comm_edges(blocks.ctypes.data, owner.ctypes.data, len(owner), int(n_workers), int(causal),
+                               edges.ctypes.data, C.byref(n)))
+    return edges[: n.value]
+
+
+def fcp_solve_matchings(edges, n_workers):
+    """Fills column 3 (sub-stage) of a contiguous int32 [E,4] edge table in place; returns Delta."""
+    if not (isinstance(edges, np.ndarray) and edges.dtype == np.int32 and edges.ndim == 2 and edges.shape[1] == 4):
+        raise ValueError("edges must be an int32 [E,4] array")
+    if len(edges) and not edges.flags["C_CONTIGUOUS"]:
+        raise ValueError("edges must be C-contiguous")
+    d = C.c_int32(0)
+    _check(_lib.fcp_solve_matchings(edges.ctypes.data if len(edges) else None, len(edges), int(n_workers), C.byref(d)))
+    return d.value
+
+
+def fcp_coalesce_stages(edges, coalesce):
+    """Returns (stage_of_edge int32 [E], n_stages)."""
+    edges = _i32(np.asarray(edges).reshape(-1, 4))
+    out = np.zeros(max(1, len(edges)), dtype=np.int32)
+    n = C.c_int32(0)
+    _check(_lib.fcp_coalesce_stages(edges.ctypes.data if len(edges) else None, len(edges), int(coalesce),
+                                    out.ctypes.data if len(edges) else None, C.byref(n)))
+    return out[: len(edges)], n.value

@@ -167,3 +167,20 @@ def test_repeated_calls_reuse_the_workspace():
         assert np.array_equal(dq, outs[0][2])               # one writer per row, fixed order
     o_ref, _ = orc.worker_fwd(wl.q(), wl.k(), wl.v(), wl.seq_lens, wl.block_size, wl.causal)
     _check("o", outs[-1][0][: o_ref.shape[0]], o_ref)
+
+
+@pytest.mark.parametrize("n_workers", [4])
+def test_distributed_share_of_the_most_loaded_worker(n_workers):
+    """Block distributor -> planner -> kernels: the share that the greedy assignment gives the most loaded of
+    `n_workers` workers on a lognormal batch (every sequence's KV resident), forward and backward.  dK / dV of
+    a share are the contributions of the owned query blocks alone, as in the oracle."""
+    import paper_2605_08524_amd as fcp
+    lens, bs = workloads.length_trace("lognormal", n_workers * 32768, seed=4) // 8, 256
+    lens = lens[lens > 0]
+    blocks, mem, comp = fcp.fcp_block_costs(lens, bs, 1)
+    owner, w_m, w_c = fcp.fcp_assign_blocks(mem, comp, n_workers)
+    heavy = int(np.argmax(w_c))
+    owned = fcp.fcp_worker_blocks(blocks, owner, heavy)
+    wl = workloads.custom_workload(lens, bs, 1, 4, 8, 2, 128, q_owned=owned, seed=77, name=f"share{heavy}of{n_workers}")
+    res = _full_parity(wl, backward=True, flags=F32)
+    assert res["o"].shape[0] == int(w_m[heavy])
