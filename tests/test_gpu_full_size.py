@@ -173,6 +173,21 @@ def _tables_exact(wl, plan):
     assert ref["n_slot_rows"] == plan["n_slot_rows"]
 
 
+def _gradient_sum_properties(wl, host, koff):
+    """Hold for any mask and size: the rows of dS sum to zero, so sum_j dK_j = 0 per sequence and KV head;
+    the rows of P sum to one, so sum_j dV_j = sum of dO over the sequence's rows and the heads of the group."""
+    G = wl.n_q_heads // wl.n_kv_heads
+    for s, L in enumerate(wl.seq_lens):
+        k0, L = int(koff[s]), int(L)
+        if L == 0:
+            continue
+        dk, dv = host["dk"][k0:k0 + L].astype(np.float64), host["dv"][k0:k0 + L].astype(np.float64)
+        assert np.max(np.abs(dk.sum(axis=0))) <= 2e-3 * np.abs(dk).sum(axis=0).max() + 1e-3, f"sum dK != 0 in seq {s}"
+        do = workloads.bf16_to_f32(wl.d_o()[k0:k0 + L]).astype(np.float64)
+        want = do.reshape(L, wl.n_kv_heads, G, wl.head_dim).sum(axis=(0, 2))
+        assert np.max(np.abs(dv.sum(axis=0) - want)) <= 2e-3 * np.abs(dv).sum(axis=0).max() + 1e-3, f"sum dV in seq {s}"
+
+
 @pytest.mark.timeout(900)
 def test_config5_training_step_full_size():
     wl = workloads.make_workload(5, 0)
@@ -198,15 +213,7 @@ def test_config5_training_step_full_size():
     accs["dq"].check()
     accs["dk"].check()
     accs["dv"].check()
-    # properties that hold at any size
-    G = wl.n_q_heads // wl.n_kv_heads
-    do = workloads.bf16_to_f32(wl.d_o()).astype(np.float64)
-    for s, L in enumerate(wl.seq_lens):
-        k0, L = int(koff[s]), int(L)
-        dk, dv = host["dk"][k0:k0 + L].astype(np.float64), host["dv"][k0:k0 + L].astype(np.float64)
-        assert np.max(np.abs(dk.sum(axis=0))) <= 2e-3 * np.abs(dk).sum(axis=0).max() + 1e-3, f"sum dK != 0 in seq {s}"
-        want = do[k0:k0 + L].reshape(L, wl.n_kv_heads, G, wl.head_dim).sum(axis=(0, 2))
-        assert np.max(np.abs(dv.sum(axis=0) - want)) <= 2e-3 * np.abs(dv).sum(axis=0).max() + 1e-3, f"sum dV in seq {s}"
+    _gradient_sum_properties(wl, host, koff)
 
 
 @pytest.mark.timeout(600)
@@ -270,3 +277,36 @@ def test_config4_multimodal_mix_sampled():
     _rows_check(wl, host, long_seq, pos, accs, False, koff, qrow)
     accs["o"].check()
     accs["lse"].check(TOL_LSE, None)
+
+
+@pytest.mark.timeout(900)
+def test_noncausal_batch_with_64_query_heads_full_size():
+    """The packed 64K-token batch without a causal mask (every pair FULL, ragged last KV block of each
+    sequence) at 64 query / 8 KV heads, the head shape of the paper's model: forward and backward."""
+    base = workloads.make_workload(2, 2)
+    wl = workloads.custom_workload(base.seq_lens, 1024, causal=0, coalesce=16, n_q_heads=64, n_kv_heads=8,
+                                   head_dim=128, seed=2, name="noncausal-64q8kv")
+    _say(f"case {wl.name}: {len(wl.seq_lens)} sequences, lengths {sorted(int(x) for x in wl.seq_lens)}")
+    host, plan = _run(wl, True, F32)
+    _tables_exact(wl, plan)
+    assert (plan["pairs"][:, 2] == 0).all()
+    for name in ("o", "lse", "dq", "dk", "dv"):
+        assert np.all(np.isfinite(host[name])), f"{name}: unwritten or non-finite rows"
+    koff, qrow = _seq_geometry(wl)
+    accs = {n: _Acc(n) for n in ("o", "lse", "dq", "dk", "dv")}
+    rng = np.random.default_rng(321)
+    t0 = time.time()
+    for s, L in enumerate(wl.seq_lens):
+        L = int(L)
+        if L <= 1000:
+            _whole_seq_check(wl, host, s, accs, True, koff, qrow)
+        else:
+            _rows_check(wl, host, s, np.concatenate([rng.integers(0, L, size=10), [0, L - 1]]), accs, True, koff, qrow)
+        _say(f"  seq {s} (L={L}) checked, {time.time() - t0:.0f} s")
+    accs["o"].check()
+    accs["lse"].check(TOL_LSE, None)
+    accs["dq"].check()
+    if accs["dk"].n:
+        accs["dk"].check()
+        accs["dv"].check()
+    _gradient_sum_properties(wl, host, koff)

@@ -89,6 +89,9 @@ EDGE = [
     ([2048], 512, 1, 3, 4, 1, 128, [(0, 0), (0, 3)]),        # a share: zig-zag pair of one sequence
     ([900, 50, 1300], 128, 1, 4, 4, 4, 64, [(0, 6), (0, 7), (1, 0), (2, 2), (2, 10)]),
     ([37], 32, 1, 1, 2, 2, 128, None),
+    ([600, 200], 256, 1, 2, 64, 8, 128, None),              # 64 query / 8 KV heads, the paper's model shape
+    ([700], 128, 1, 3, 6, 2, 64, None),                     # odd group size
+    ([1500, 100], 512, 0, 0, 16, 2, 128, None),             # non-causal, groups of 8
 ]
 
 
