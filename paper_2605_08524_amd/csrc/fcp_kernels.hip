@@ -313,7 +313,8 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
     const QItem it = a.items[item_idx];
-    const int q_rows = it.q_rows[sub], tile_off_q = it.tile_off[sub], head = it.head[sub];
+    // selects, not it.q_rows[sub]: a run-time index would put the whole item into private memory
+    const int q_rows = (sub ? it.q_rows[1] : it.q_rows[0]), tile_off_q = (sub ? it.tile_off[1] : it.tile_off[0]), head = (sub ? it.head[1] : it.head[0]);
     const int kvh = it.head[0] / group;
     const int my_row = wq * 32 + l32;                        // row inside the sub-tile
     const bool row_ok = my_row < q_rows;
@@ -325,7 +326,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     // Q^T fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d per k-chunk.
     bf16x8 qf[KC];
     {
-      const uint16_t* qp = a.q + (int64_t)(it.q_start[sub] + my_row) * q_row_stride + (int64_t)head * D + 8 * g;
+      const uint16_t* qp = a.q + (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) * q_row_stride + (int64_t)head * D + 8 * g;
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) {
         u32x4 v = {0, 0, 0, 0};
@@ -520,7 +521,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     if (row_ok) {
       // the only slot of its query block: this is the final result, not a partial
       const bool to_final = it.pad[0] != 0;
-      const int64_t row = to_final ? (int64_t)(it.q_start[sub] + my_row) : (int64_t)(it.out_row[sub] + my_row);
+      const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
       const int64_t off = row * q_row_stride + (int64_t)head * D;
       if (to_final && !a.o_is_f32) {
         uint16_t* op = reinterpret_cast<uint16_t*>(a.o) + off;
@@ -1142,7 +1143,7 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
     const QItem it = a.dq_items[item_idx];
-    const int q_start = it.q_start[sub], q_rows = it.q_rows[sub], tile_off_q = it.tile_off[sub], head = it.head[sub];
+    const int q_start = (sub ? it.q_start[1] : it.q_start[0]), q_rows = (sub ? it.q_rows[1] : it.q_rows[0]), tile_off_q = (sub ? it.tile_off[1] : it.tile_off[0]), head = (sub ? it.head[1] : it.head[0]);
     const int kvh = it.head[0] / group;
     const int my_row = wq * 32 + l32;
     const bool row_ok = my_row < q_rows;
