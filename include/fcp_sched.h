@@ -35,6 +35,25 @@ int fcp_block_costs(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
                     fcp_block* blocks, int64_t* mem, int64_t* comp, int32_t* n_blocks);
 
 /*
+ * fcp_pack_units -- scheduling units: short sequences share a unit, every other block is its own.
+ *
+ * Paper: section "Block Distributor", sharding policy (sequences shorter than the block size are
+ * packed into as few blocks as possible and computed through the variable-length path).  The paper
+ * names no packing rule; this is first-fit decreasing: the blocks of single-block sequences with
+ * fewer than block_size tokens, in descending length (equal lengths: lower block index first), each
+ * go into the first open unit that still has room for them, else open a new unit.  Units are
+ * numbered by their lowest member block.  The kernels need nothing for this: a unit's blocks stay
+ * separate ragged blocks of the planner; the unit only makes them travel and get assigned together.
+ * blocks / mem / comp: as written by fcp_block_costs.  unit_of_block[n_blocks]: out.
+ * unit_mem / unit_comp: out, summed costs, capacity *n_units on entry (n_blocks always suffices);
+ * *n_units: count on return.  Feed unit_mem / unit_comp to fcp_assign_blocks; the owner of block b
+ * is then owner[unit_of_block[b]].
+ */
+int fcp_pack_units(const fcp_block* blocks, const int64_t* mem, const int64_t* comp, int32_t n_blocks,
+                   int32_t block_size, int32_t* unit_of_block, int64_t* unit_mem, int64_t* unit_comp,
+                   int32_t* n_units);
+
+/*
  * fcp_assign_blocks -- Greedy Load-Balanced Assignment (the paper's appendix algorithm of that name).
  *
  * m_hat = sum(mem) / N, c_hat = sum(comp) / N.  Blocks are taken in descending order of

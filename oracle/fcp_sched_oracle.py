@@ -12,6 +12,8 @@ What it follows (all from the paper):
   block, c_i = number of unmasked (query row, key column) score entries of the block's
   query rows, per head; the paper gives no formula ("estimated from the context length
   of the source sequence").
+* Short sequences (section "Block Distributor", sharding policy) are packed into shared units by
+  first-fit decreasing; the paper asks for as few blocks as possible and names no rule.
 * Greedy Load-Balanced Assignment (appendix algorithm of that name): average loads,
   descending sort by max(m_i / m_hat, c_i / c_hat), then every block goes to the
   eligible worker with the smallest max(alpha (m_w + m_i) / m_hat, beta (c_w + c_i) / c_hat).
@@ -66,6 +68,40 @@ def block_costs(seq_lens, block_size, causal=1):
                 c.append((hi - lo) * L)
         row += L
     return np.asarray(blocks, dtype=np.int64).reshape(-1, 4), m, c
+
+
+# --------------------------------------------------------------------------
+# packing of short sequences into scheduling units
+# --------------------------------------------------------------------------
+def pack_units(blocks, m, c, block_size):
+    """Scheduling units: a sequence shorter than a block does not get a block of its own but shares one with
+    other short sequences (section "Block Distributor", sharding policy: short sequences are packed into as
+    few blocks as possible and run through the variable-length path).  The paper names no packing rule;
+    read here as first-fit decreasing: the short sequences in descending length (equal lengths in block
+    order) each go into the first open unit with room, else open a new one.  Every block of a sequence that
+    has at least block_size tokens is a unit by itself.  Units are numbered by their first member block.
+    Returns (unit_of_block [K], unit_m [U], unit_c [U])."""
+    K = len(m)
+    n_in_seq = {}
+    for b in blocks:
+        n_in_seq[int(b[0])] = n_in_seq.get(int(b[0]), 0) + 1
+    short = [i for i in range(K) if n_in_seq[int(blocks[i][0])] == 1 and m[i] < block_size]
+    bins = []                     # [free tokens, member list]
+    for i in sorted(short, key=lambda i: -m[i]):
+        for bn in bins:
+            if bn[0] >= m[i]:
+                bn[0] -= m[i]
+                bn[1].append(i)
+                break
+        else:
+            bins.append([block_size - m[i], [i]])
+    groups = [[i] for i in range(K) if i not in set(short)] + [sorted(bn[1]) for bn in bins]
+    groups.sort(key=lambda g: g[0])
+    unit_of_block = [-1] * K
+    for u, g in enumerate(groups):
+        for i in g:
+            unit_of_block[i] = u
+    return unit_of_block, [sum(m[i] for i in g) for g in groups], [sum(c[i] for i in g) for g in groups]
 
 
 # --------------------------------------------------------------------------

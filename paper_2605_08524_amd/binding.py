@@ -31,7 +31,7 @@ EXPORTS = (
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_last_error", "fcp_device_info",
     "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
-    "fcp_coalesce_stages",
+    "fcp_coalesce_stages", "fcp_pack_units",
 )
 
 
@@ -78,6 +78,7 @@ def _load():
     lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     i64p = C.POINTER(C.c_int64)
     lib.fcp_block_costs.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, i32p]
+    lib.fcp_pack_units.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, i32p]
     lib.fcp_assign_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int64,
                                       C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fcp_worker_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, i32p]
@@ -236,6 +237,18 @@ def fcp_block_costs(seq_lens, block_size, causal=1):
     _check(_lib.fcp_block_costs(sl.ctypes.data_as(i32p), len(sl), int(block_size), int(causal),
                                 blocks.ctypes.data, mem.ctypes.data, comp.ctypes.data, C.byref(n)))
     return blocks[: n.value], mem[: n.value], comp[: n.value]
+
+
+def fcp_pack_units(blocks, mem, comp, block_size):
+    """Returns (unit_of_block int32 [n], unit_mem int64 [U], unit_comp int64 [U])."""
+    blocks, mem, comp = _i32(np.asarray(blocks).reshape(-1, 4)), _i64(mem), _i64(comp)
+    n = len(mem)
+    unit = np.full(max(1, n), -1, dtype=np.int32)
+    u_m, u_c = np.zeros(max(1, n), dtype=np.int64), np.zeros(max(1, n), dtype=np.int64)
+    cnt = C.c_int32(n)
+    _check(_lib.fcp_pack_units(blocks.ctypes.data, mem.ctypes.data, comp.ctypes.data, n, int(block_size),
+                               unit.ctypes.data, u_m.ctypes.data, u_c.ctypes.data, C.byref(cnt)))
+    return unit[:n], u_m[: cnt.value], u_c[: cnt.value]
 
 
 def fcp_assign_blocks(mem, comp, n_workers, alpha=1.0, beta=1.0, mem_limit=0, delta=0.0):

@@ -47,6 +47,53 @@ extern "C" int fcp_block_costs(const int32_t* seq_lens, int32_t n_seqs, int32_t 
   return FCP_OK;
 }
 
+extern "C" int fcp_pack_units(const fcp_block* blocks, const int64_t* mem, const int64_t* comp, int32_t n_blocks,
+                              int32_t block_size, int32_t* unit_of_block, int64_t* unit_mem, int64_t* unit_comp,
+                              int32_t* n_units) {
+  if (n_blocks < 0 || block_size <= 0 || !n_units || (n_blocks > 0 && (!blocks || !mem || !comp || !unit_of_block || !unit_mem || !unit_comp))) {
+    set_error("fcp_pack_units: NULL argument, negative count or block_size <= 0"); return FCP_ERR_INVALID_ARG;
+  }
+  // a short sequence = a sequence with one block of fewer than block_size tokens
+  std::vector<int32_t> shorts;
+  for (int i = 0; i < n_blocks; i++) {
+    const bool alone = (i == 0 || blocks[i - 1].seq != blocks[i].seq) && (i + 1 == n_blocks || blocks[i + 1].seq != blocks[i].seq);
+    if (alone && mem[i] < block_size) shorts.push_back(i);
+  }
+  std::stable_sort(shorts.begin(), shorts.end(), [&](int32_t a, int32_t b) { return mem[a] > mem[b]; });
+  // first fit: bins in the order they were opened
+  std::vector<int64_t> room;
+  std::vector<int32_t> bin_of(n_blocks, -1), bin_first;
+  for (int32_t i : shorts) {
+    size_t b = 0;
+    while (b < room.size() && room[b] < mem[i]) b++;
+    if (b == room.size()) { room.push_back(block_size); bin_first.push_back(i); }
+    room[b] -= mem[i];
+    bin_of[i] = (int32_t)b;
+    bin_first[b] = std::min(bin_first[b], i);
+  }
+  // number the units by their lowest member block
+  std::vector<int32_t> unit_of_bin(room.size(), -1);
+  int32_t n = 0;
+  for (int i = 0; i < n_blocks; i++) {
+    if (bin_of[i] < 0) unit_of_block[i] = n++;
+    else {
+      if (bin_first[bin_of[i]] == i) unit_of_bin[bin_of[i]] = n++;
+      unit_of_block[i] = -1 - bin_of[i];       // resolved below, once its bin has a number
+    }
+  }
+  const int32_t cap = *n_units;
+  *n_units = n;
+  if (cap < n) { set_error("fcp_pack_units: capacity %d < %d units", cap, n); return FCP_ERR_BUFFER_TOO_SMALL; }
+  std::fill(unit_mem, unit_mem + n, 0);
+  std::fill(unit_comp, unit_comp + n, 0);
+  for (int i = 0; i < n_blocks; i++) {
+    if (unit_of_block[i] < 0) unit_of_block[i] = unit_of_bin[-1 - unit_of_block[i]];
+    unit_mem[unit_of_block[i]] += mem[i];
+    unit_comp[unit_of_block[i]] += comp[i];
+  }
+  return FCP_OK;
+}
+
 extern "C" int fcp_assign_blocks(const int64_t* mem, const int64_t* comp, int32_t n_blocks, int32_t n_workers,
                                  double alpha, double beta, int64_t mem_limit, double delta,
                                  int32_t* owner, int64_t* worker_mem, int64_t* worker_comp) {

@@ -181,3 +181,34 @@ def test_worker_share_feeds_the_planner():
         assert np.array_equal(plan["pairs"], np.asarray(ref["pairs"], dtype=np.int32).reshape(-1, 4))
         need = set(plan["pairs"][:, 1].tolist())
         assert {kb for kb in need if owner[kb] != w} == set(edges[edges[:, 1] == w][:, 2].tolist())
+
+
+def test_pack_units_matches_oracle():
+    rng = np.random.default_rng(12)
+    cases = [([7, 25, 3, 6, 4, 10], 10), ([13, 0, 4, 9, 1], 4), ([5], 8), ([], 8)]
+    for _ in range(6):
+        lens = np.where(rng.random(60) < 0.7, rng.integers(1, 1024, size=60), rng.integers(1024, 9000, size=60))
+        cases.append((lens.tolist(), 1024))
+    for lens, bs in cases:
+        blocks, m, c = sch.block_costs(lens, bs, 1)
+        ref = sch.pack_units(blocks, m, c, bs)
+        unit, u_m, u_c = fcp.fcp_pack_units(blocks, m, c, bs)
+        assert unit.tolist() == ref[0] and u_m.tolist() == ref[1] and u_c.tolist() == ref[2]
+
+
+def test_units_flow_through_assignment_and_planner():
+    """Short sequences assigned as shared units: every member of a unit lands on the same worker, and the
+    worker tables built from it are what the planner accepts."""
+    rng = np.random.default_rng(13)
+    lens = np.where(rng.random(80) < 0.75, rng.integers(16, 512, size=80), rng.integers(2000, 12000, size=80))
+    bs, n = 1024, 4
+    blocks, mem, comp = fcp.fcp_block_costs(lens, bs, 1)
+    unit, u_m, u_c = fcp.fcp_pack_units(blocks, mem, comp, bs)
+    assert len(u_m) < len(mem) and u_m[np.bincount(unit) > 1].max() <= bs
+    u_owner, w_m, w_c = fcp.fcp_assign_blocks(u_m, u_c, n)
+    owner = u_owner[unit]
+    assert w_m.sum() == mem.sum() and np.array_equal(np.bincount(owner, weights=mem, minlength=n).astype(np.int64), w_m)
+    for w in range(n):
+        q_owned = fcp.fcp_worker_blocks(blocks, owner, w)
+        plan = fcp.fcp_plan_blocks(lens, bs, 1, 16, q_owned)
+        assert int(plan["q_blocks"][:, 3].sum()) == int(w_m[w])

@@ -287,3 +287,54 @@ def test_coalescer_keeps_per_stage_bounds():
             bound = delta if c <= 0 else c
             assert max(s.count(u) for u in set(s)) <= bound
             assert max(r.count(w) for w in set(r)) <= bound
+
+
+# ------------------------------------------------------------------ packing of short sequences
+def _min_bins_brute(sizes, cap):
+    best = len(sizes)
+    for assign in itertools.product(range(len(sizes)), repeat=len(sizes)):
+        load = {}
+        for sz, b in zip(sizes, assign):
+            load[b] = load.get(b, 0) + sz
+        if max(load.values()) <= cap:
+            best = min(best, len(load))
+    return best
+
+
+def test_pack_units_fits_and_is_near_the_minimum():
+    """Every unit of short sequences holds at most block_size tokens; first-fit decreasing needs at most
+    11/9 OPT + 6/9 units (Dosa's bound), OPT by exhaustive search; long sequences are left alone."""
+    rng = np.random.default_rng(8)
+    bs = 16
+    for _ in range(6):
+        short = rng.integers(1, bs, size=6).tolist()
+        lens = [40] + short[:3] + [16] + short[3:] + [33]
+        blocks, m, c = sch.block_costs(lens, bs, 1)
+        unit, um, uc = sch.pack_units(blocks, m, c, bs)
+        assert sum(um) == sum(m) and sum(uc) == sum(c)
+        n_long = sum(1 for b in blocks if int(lens[int(b[0])]) >= bs)
+        sizes = {}
+        for i, b in enumerate(blocks):
+            if lens[int(b[0])] >= bs:
+                assert unit.count(unit[i]) == 1                      # a unit of its own
+            else:
+                sizes.setdefault(unit[i], []).append(m[i])
+        assert all(sum(v) <= bs for v in sizes.values())
+        assert len(um) == n_long + len(sizes)
+        opt = _min_bins_brute(short, bs)
+        assert opt <= len(sizes) <= (11 * opt + 6) // 9
+        # units are numbered by their first member
+        firsts = [unit.index(u) for u in range(len(um))]
+        assert firsts == sorted(firsts)
+
+
+def test_pack_units_hand_worked():
+    """Block size 10, lengths 7, 25, 3, 6, 4, 10 -> blocks of 7 | 10, 10, 5 | 3 | 6 | 4 | 10 tokens.  Short
+    sequences: blocks 0 (7), 4 (3), 5 (6), 6 (4); the 5-token tail of the long sequence and the full 10-token
+    block are not.  First-fit decreasing: 7 opens A; 6 does not fit A, opens B; 4 fits B (6 + 4); 3 fits A (7 + 3)."""
+    blocks, m, c = sch.block_costs([7, 25, 3, 6, 4, 10], 10, 1)
+    unit, um, uc = sch.pack_units(blocks, m, c, 10)
+    assert m == [7, 10, 10, 5, 3, 6, 4, 10]
+    assert unit == [0, 1, 2, 3, 0, 4, 4, 5]
+    assert um == [10, 10, 10, 5, 10, 10]
+    assert uc[0] == c[0] + c[4] and uc[4] == c[5] + c[6]
