@@ -27,9 +27,9 @@ PEAK_HBM_GBS = 8000.0
 # plain copy of known size in the same runs (profiles/cfg5_training_step_hbm_traffic.txt); None
 # for a workload or kernel that has not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 3.191e9,
-    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 7.128e9,
-    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 3.332e9,
+    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.805e9,
+    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.459e9,
+    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 3.220e9,
 }
 
 
