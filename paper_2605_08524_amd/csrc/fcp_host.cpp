@@ -118,9 +118,17 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   std::vector<int32_t> slots_of(p->n_q_blocks, 0);
   for (int s = 0; s < p->n_slots; s++) slots_of[p->slots[s].q_blk]++;
   const bool direct = (p->flags & FCP_FLAG_DIRECT_SINGLE) != 0;
+  {
+    // Chunk of the merge: small enough for kMergeMinItems work items (the kernel walks the slots of a chunk one
+    // after the other, so a few long items leave most of the chip idle), a multiple of 32 entries, at most kMergeChunk.
+    int64_t entries = 0;
+    for (int b = 0; b < p->n_q_blocks; b++)
+      if (!(direct && slots_of[b] == 1)) entries += (int64_t)p->q_blocks[b].tok_len * p->n_q_heads;
+    L->merge_chunk = (int)std::min<int64_t>(kMergeChunk, std::max<int64_t>(32, ceil_div(ceil_div(entries, kMergeMinItems), 32) * 32));
+  }
   for (int b = 0; b < p->n_q_blocks; b++) {
     if (!(direct && slots_of[b] == 1))
-      L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, kMergeChunk);
+      L->n_merge_items += ceil_div((int64_t)p->q_blocks[b].tok_len * p->n_q_heads, L->merge_chunk);
     {
       const int G = p->n_q_heads / p->n_kv_heads;
       const int64_t n_tiles = ceil_div(p->q_blocks[b].tok_len, kFwdTileM);
@@ -511,8 +519,8 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
       const fcp_block& qb = p->q_blocks[b];
       if ((p->flags & FCP_FLAG_DIRECT_SINGLE) && slot_begin[b + 1] - slot_begin[b] == 1) continue;   // written by the forward
       const int64_t total = (int64_t)qb.tok_len * p->n_q_heads;
-      for (int64_t off = 0; off < total; off += kMergeChunk) {
-        mi[n++] = {(int32_t)((int64_t)qb.tok_start * p->n_q_heads + off), (int32_t)std::min<int64_t>(kMergeChunk, total - off),
+      for (int64_t off = 0; off < total; off += L.merge_chunk) {
+        mi[n++] = {(int32_t)((int64_t)qb.tok_start * p->n_q_heads + off), (int32_t)std::min<int64_t>(L.merge_chunk, total - off),
                    slot_begin[b], slot_begin[b + 1] - slot_begin[b], (int32_t)off, 0, 0, 0};
       }
     }

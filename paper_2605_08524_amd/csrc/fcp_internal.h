@@ -12,7 +12,8 @@ namespace fcp {
 constexpr int kNumXcd = 8;          // MI355X: 8 XCDs, each with its own L2; workgroup b runs on XCD b % 8
 constexpr int kFwdTileM = 128;      // query rows per query-stationary work item (4 waves x 32 rows)
 constexpr int kBwdTileN = 128;      // KV rows per backward work item (4 waves x 32 rows)
-constexpr int kMergeChunk = 1024;   // (row, head) entries per merge work item
+constexpr int kMergeChunk = 1024;   // most (row, head) entries per merge work item (fewer when there is little to merge)
+constexpr int kMergeMinItems = 2048;  // the merge aims at this many work items at least: 8 per compute unit
 
 // Device-side records (all int32 so the host can build them as plain arrays).
 struct DevPair { int32_t kv_start, kv_len, kind, pad; };
@@ -45,6 +46,7 @@ struct WsHeader {
 struct WsLayout {
   int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, n_dq_items, t_q, t_kv;
   int fwd_tile_m;   // query rows per forward item, chosen per problem
+  int merge_chunk;  // (row, head) entries per merge work item, chosen per problem
   size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_dls, off_lse2, total;
 };
 
