@@ -172,6 +172,48 @@ def test_repeated_calls_reuse_the_workspace():
     _check("o", outs[-1][0][: o_ref.shape[0]], o_ref)
 
 
+def test_whole_step_replays_from_a_hip_graph():
+    """The launches of a step (forward, merge, backward) captured into one HIP graph: the library allocates
+    nothing, waits for nothing and clears its queue counters inside the kernels, so a replay is the step.
+    Every replay, with eager work and synchronisations in between, must give the eager result bit for bit."""
+    from paper_2605_08524_amd.harness import DevicePath
+    dev = torch.device("cuda:0")
+    wl = workloads.custom_workload([700, 333, 129], 128, 1, 2, 4, 2, 128, seed=21, name="graph")
+    _say(f"case {wl.name}")
+    dp = DevicePath(wl, dev, flags=F32, backward=True)
+    outs = ("o", "lse", "dq", "dk", "dv")
+
+    def poison():
+        for name in outs + ("o_part", "lse_part"):
+            getattr(dp, name).fill_(float("nan"))
+
+    def snapshot():
+        torch.cuda.synchronize(dev)
+        return [getattr(dp, name).float().cpu().numpy().copy() for name in outs]
+
+    poison()
+    dp.fwd(); dp.merge(); dp.bwd()
+    eager = snapshot()
+    assert all(np.isfinite(x[: dp.problem.t_q if i < 3 else dp.problem.t_kv]).all() for i, x in enumerate(eager))
+    side = torch.cuda.Stream(device=dev)
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize(dev)
+    with torch.cuda.graph(graph, stream=side):
+        dp.stream = torch.cuda.current_stream(dev)          # the capturing stream
+        dp.fwd(); dp.merge(); dp.bwd()
+    dp.stream = None
+    for rep in range(3):
+        poison()                                             # eager work between the replays
+        torch.cuda.synchronize(dev)
+        graph.replay()
+        got = snapshot()
+        for name, x, y in zip(outs, got, eager):
+            assert np.array_equal(x, y, equal_nan=True), f"replay {rep}: {name} differs from the eager result"
+        if rep == 1:                                         # an eager step in between leaves the counters clean too
+            dp.fwd(); dp.merge(); dp.bwd()
+            torch.cuda.synchronize(dev)
+
+
 @pytest.mark.parametrize("n_workers", [4])
 def test_distributed_share_of_the_most_loaded_worker(n_workers):
     """Block distributor -> planner -> kernels: the share that the greedy assignment gives the most loaded of
