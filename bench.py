@@ -216,6 +216,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-step", action="store_true",
                     help="every query block goes through the partial buffers and the merge, also those with one slot")
+    ap.add_argument("--bf16-partials", action="store_true", help="keep the partial O buffer in bf16 (FCP_FLAG_PART_BF16)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
@@ -236,7 +237,7 @@ def main():
         distribute(args)
         return
     import torch
-    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, fcp_device_info, workloads
+    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, FCP_FLAG_PART_BF16, fcp_device_info, workloads
     from paper_2605_08524_amd.harness import DevicePath
 
     dev = torch.device("cuda:0")
@@ -247,6 +248,8 @@ def main():
     t0 = time.perf_counter()
     # a query block with one slot needs no reduction: the forward writes it straight to the final O / LSE
     flags = (0 if args.two_step else FCP_FLAG_DIRECT_SINGLE) | (FCP_FLAG_O_F32 if backward else 0)
+    if args.bf16_partials:
+        flags |= FCP_FLAG_PART_BF16
     dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream)
     torch.cuda.synchronize(dev)
     setup_s = time.perf_counter() - t0
@@ -306,7 +309,7 @@ def main():
     merged = cnt > (1 if (flags & FCP_FLAG_DIRECT_SINGLE) else 0)
     merged_rows = int(qb[merged, 3].sum()) if len(qb) else 0
     part_rows = int((cnt[merged] * qb[merged, 3]).sum()) if len(qb) else 0
-    merge_bytes = (part_rows * wl.n_q_heads * (wl.head_dim * 4 + 4)
+    merge_bytes = (part_rows * wl.n_q_heads * (wl.head_dim * (2 if (flags & FCP_FLAG_PART_BF16) else 4) + 4)
                    + merged_rows * wl.n_q_heads * (wl.head_dim * (4 if backward else 2) + 4))
     info = fcp_device_info()
     out = {

@@ -55,6 +55,10 @@ typedef struct { int32_t q_blk, pair_begin, n_pairs, row_start; } fcp_slot;
 
 enum {
   FCP_FLAG_O_F32 = 1,            /* the final O is fp32 instead of bf16 (the backward then reads fp32 O) */
+  FCP_FLAG_PART_BF16 = 4,        /* the partial O buffer (o_part) holds bf16 instead of fp32: half the memory and half the
+                                    traffic of the partials; LSE partials stay fp32.  Set it for every call on a problem.
+                                    A final O merged from bf16 partials carries bf16 rounding whatever its own dtype:
+                                    meant for forward-only use (the backward's D = rowsum(dO o O) inherits it). */
   FCP_FLAG_DIRECT_SINGLE = 2     /* a query block with ONE slot needs no reduction: fcp_block_attn_fwd_out writes its
                                     result straight to the final o / lse and fcp_merge_partials leaves it alone.
                                     Set it before fcp_workspace_bytes / fcp_queue_build and keep it for every call
@@ -134,11 +138,11 @@ int fcp_queue_build(const fcp_problem* p, void* workspace, size_t workspace_byte
  * For slot s of query block b, rows r < tok_len(b):
  *   o_part [row_start(s) + r, h, :] = softmax over the slot's visible keys (normalised)
  *   lse_part[row_start(s) + r, h]   = ln sum exp(scale * q.k) over those keys
- * q [T_q,Hq,d], k, v [T_kv,Hkv,d]: device bf16.  o_part [n_slot_rows,Hq,d], lse_part
+ * q [T_q,Hq,d], k, v [T_kv,Hkv,d]: device bf16.  o_part [n_slot_rows,Hq,d] (fp32, or bf16 with FCP_FLAG_PART_BF16), lse_part
  * [n_slot_rows,Hq]: device fp32, fully overwritten.  workspace: as built by fcp_queue_build.
  */
 int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
-                       float* o_part, float* lse_part, void* workspace, void* stream);
+                       void* o_part, float* lse_part, void* workspace, void* stream);
 
 /*
  * fcp_block_attn_fwd_out -- fcp_block_attn_fwd that also knows the final outputs.
@@ -152,7 +156,7 @@ int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const
  * fcp_block_attn_fwd and ignores o / lse.  o [T_q,Hq,d], lse [T_q,Hq]: device.
  */
 int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, const void* v,
-                           float* o_part, float* lse_part, void* o, float* lse,
+                           void* o_part, float* lse_part, void* o, float* lse,
                            void* workspace, void* stream);
 
 /*
@@ -164,7 +168,7 @@ int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, c
  * o [T_q,Hq,d]: device, bf16 (default) or fp32 (FCP_FLAG_O_F32); lse [T_q,Hq]: device fp32.
  * With FCP_FLAG_DIRECT_SINGLE, query blocks with one slot are skipped (fcp_block_attn_fwd_out wrote them).
  */
-int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* lse_part,
+int fcp_merge_partials(const fcp_problem* p, const void* o_part, const float* lse_part,
                        void* o, float* lse, void* workspace, void* stream);
 
 /*

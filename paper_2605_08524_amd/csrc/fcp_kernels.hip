@@ -217,7 +217,7 @@ constexpr float kRescaleSlack = 8.0f;   // log2 units
 
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
-  float* o_part; float* lse_part;
+  void* o_part; float* lse_part; int32_t part_is_bf16;
   void* o; float* lse; int32_t o_is_f32;     // final outputs for query blocks with a single slot (or NULL)
   WsHeader* hdr; const DevPair* pairs; const QItem* items;
   int32_t n_q_heads, n_kv_heads;
@@ -523,8 +523,8 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       const bool to_final = it.pad[0] != 0;
       const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
       const int64_t off = row * q_row_stride + (int64_t)head * D;
-      if (to_final && !a.o_is_f32) {
-        uint16_t* op = reinterpret_cast<uint16_t*>(a.o) + off;
+      if (to_final ? !a.o_is_f32 : a.part_is_bf16) {
+        uint16_t* op = reinterpret_cast<uint16_t*>(to_final ? a.o : a.o_part) + off;
 #pragma unroll
         for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -533,7 +533,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
             *reinterpret_cast<u32x2*>(op + dt * 32 + 8 * q4 + 4 * g) = h;
           }
       } else {
-        float* op = (to_final ? reinterpret_cast<float*>(a.o) : a.o_part) + off;
+        float* op = reinterpret_cast<float*>(to_final ? a.o : a.o_part) + off;
 #pragma unroll
         for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -557,9 +557,9 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
 // One group of D/4 lanes owns one (row, head) entry: a float4 of the head vector per lane.
 // =====================================================================================
 struct MergeArgs {
-  const float* o_part; const float* lse_part; void* o; float* lse;
+  const void* o_part; const float* lse_part; void* o; float* lse;
   const MergeItem* items; const int32_t* slot_rh;
-  int32_t o_is_f32;
+  int32_t o_is_f32, part_is_bf16;
 };
 
 template <int D>
@@ -592,7 +592,13 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
         xx[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (ok[u]) {
           ll[u] = a.lse_part[base + u * EPP];
-          xx[u] = *reinterpret_cast<const f32x4*>(a.o_part + (base + u * EPP) * D + ln * 4);
+          if (a.part_is_bf16) {
+            const u32x2 h = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.o_part) + (base + u * EPP) * D + ln * 4);
+            xx[u] = f32x4{__builtin_bit_cast(float, h[0] << 16), __builtin_bit_cast(float, h[0] & 0xffff0000u),
+                          __builtin_bit_cast(float, h[1] << 16), __builtin_bit_cast(float, h[1] & 0xffff0000u)};
+          } else {
+            xx[u] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.o_part) + (base + u * EPP) * D + ln * 4);
+          }
         }
       }
     };
@@ -1297,7 +1303,7 @@ extern "C" int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int3
 }
 
 static int launch_fwd(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,
-                      float* o_part, float* lse_part, void* o, float* lse, void* workspace, void* stream) {
+                      void* o_part, float* lse_part, void* o, float* lse, void* workspace, void* stream) {
   int rc = validate_problem(p);
   if (rc) return rc;
   WsLayout L;
@@ -1313,7 +1319,7 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
-  a.o_part = o_part; a.lse_part = lse_part;
+  a.o_part = o_part; a.lse_part = lse_part; a.part_is_bf16 = (p->flags & FCP_FLAG_PART_BF16) ? 1 : 0;
   a.o = direct ? o : nullptr; a.lse = direct ? lse : nullptr;
   a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
   a.hdr = reinterpret_cast<WsHeader*>(ws);
@@ -1328,17 +1334,17 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
 }
 
 extern "C" int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                  float* o_part, float* lse_part, void* workspace, void* stream) {
+                                  void* o_part, float* lse_part, void* workspace, void* stream) {
   return launch_fwd("fcp_block_attn_fwd", p, q, k, v, o_part, lse_part, nullptr, nullptr, workspace, stream);
 }
 
 extern "C" int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                      float* o_part, float* lse_part, void* o, float* lse,
+                                      void* o_part, float* lse_part, void* o, float* lse,
                                       void* workspace, void* stream) {
   return launch_fwd("fcp_block_attn_fwd_out", p, q, k, v, o_part, lse_part, o, lse, workspace, stream);
 }
 
-extern "C" int fcp_merge_partials(const fcp_problem* p, const float* o_part, const float* lse_part,
+extern "C" int fcp_merge_partials(const fcp_problem* p, const void* o_part, const float* lse_part,
                                   void* o, float* lse, void* workspace, void* stream) {
   int rc = validate_problem(p);
   if (rc) return rc;
@@ -1353,6 +1359,7 @@ extern "C" int fcp_merge_partials(const fcp_problem* p, const float* o_part, con
   a.items = reinterpret_cast<const MergeItem*>(ws + L.off_merge_items);
   a.slot_rh = reinterpret_cast<const int32_t*>(ws + L.off_slot_rh);
   a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
+  a.part_is_bf16 = (p->flags & FCP_FLAG_PART_BF16) ? 1 : 0;
   if (p->head_dim == 128) hipLaunchKernelGGL(merge_kernel<128>, dim3((unsigned)L.n_merge_items), dim3(256), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(merge_kernel<64>, dim3((unsigned)L.n_merge_items), dim3(256), 0, (hipStream_t)stream, a);
   return check_launch("fcp_merge_partials");

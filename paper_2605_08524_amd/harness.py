@@ -29,7 +29,8 @@ class DevicePath:
         self.v = to_dev_bf16(wl.v(), device)
         f32 = dict(dtype=torch.float32, device=device)
         nan = float("nan")
-        self.o_part = torch.full((max(1, p.n_slot_rows), Hq, d), nan, **f32)
+        part_dtype = torch.bfloat16 if (flags & B.FCP_FLAG_PART_BF16) else torch.float32
+        self.o_part = torch.full((max(1, p.n_slot_rows), Hq, d), nan, dtype=part_dtype, device=device)
         self.lse_part = torch.full((max(1, p.n_slot_rows), Hq), nan, **f32)
         o_dtype = torch.float32 if (flags & B.FCP_FLAG_O_F32) else torch.bfloat16
         self.o = torch.full((max(1, p.t_q), Hq, d), nan, dtype=o_dtype, device=device)
@@ -81,7 +82,7 @@ def run_path(wl, device, backward=False, flags=0):
         dp.bwd()
     torch.cuda.synchronize(device)
     p = dp.problem
-    out = dict(plan=dp.plan, o_part=dp.o_part[: p.n_slot_rows].cpu().numpy(),
+    out = dict(plan=dp.plan, o_part=dp.o_part[: p.n_slot_rows].float().cpu().numpy(),
                lse_part=dp.lse_part[: p.n_slot_rows].cpu().numpy(),
                o=dp.o[: p.t_q].float().cpu().numpy(), lse=dp.lse[: p.t_q].cpu().numpy())
     if backward:
