@@ -340,6 +340,7 @@ def main():
             "avg_launch_ms": round(stage_ms[dom], 4),
         },
         "grid": info, "setup_s": round(setup_s, 2),
+        "host_ms": {"plan_blocks": round(dp.plan_ms, 3), "queue_build": round(dp.queue_build_ms, 3)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl) if backward else None

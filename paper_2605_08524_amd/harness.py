@@ -3,6 +3,8 @@ workload's tensors with PyTorch, allocates outputs and the workspace, and calls 
 No arithmetic of the method happens here."""
 from __future__ import annotations
 
+import time
+
 import numpy as np
 import torch
 
@@ -20,7 +22,9 @@ class DevicePath:
 
     def __init__(self, wl, device, flags=0, backward=False, stream=None):
         self.wl, self.device, self.stream = wl, device, stream
+        t0 = time.perf_counter()
         self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+        self.plan_ms = (time.perf_counter() - t0) * 1e3              # host: block table, pair list, slots
         self.problem = B.Problem(self.plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, 0.0, flags)
         p = self.problem
         Hq, Hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
@@ -39,7 +43,10 @@ class DevicePath:
         self.ws = torch.zeros(self.ws_bytes + 256, dtype=torch.uint8, device=device)
         off = (-self.ws.data_ptr()) % 256
         self.ws_ptr = self.ws.data_ptr() + off
+        torch.cuda.synchronize(device)
+        t0 = time.perf_counter()
         B.fcp_queue_build(p, self.ws_ptr, self.ws_bytes, stream)
+        self.queue_build_ms = (time.perf_counter() - t0) * 1e3     # host: work items + one upload (returns when it is done)
         if backward:
             self.d_o = to_dev_bf16(wl.d_o(), device)
             self.dq = torch.full((max(1, p.t_q), Hq, d), nan, **f32)
