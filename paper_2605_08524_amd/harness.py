@@ -20,12 +20,12 @@ def to_dev_bf16(bits: np.ndarray, device) -> torch.Tensor:
 class DevicePath:
     """Holds the device buffers of one workload and runs the path's calls on them."""
 
-    def __init__(self, wl, device, flags=0, backward=False, stream=None):
+    def __init__(self, wl, device, flags=0, backward=False, stream=None, softmax_scale=0.0):
         self.wl, self.device, self.stream = wl, device, stream
         t0 = time.perf_counter()
         self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
         self.plan_ms = (time.perf_counter() - t0) * 1e3              # host: block table, pair list, slots
-        self.problem = B.Problem(self.plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, 0.0, flags)
+        self.problem = B.Problem(self.plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, softmax_scale, flags)
         p = self.problem
         Hq, Hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
         self.q = to_dev_bf16(wl.q(), device)
@@ -80,9 +80,9 @@ class DevicePath:
                                 self.dq, self.ws_ptr, self.stream)
 
 
-def run_path(wl, device, backward=False, flags=0):
+def run_path(wl, device, backward=False, flags=0, softmax_scale=0.0):
     """One pass of the whole path; returns host copies (numpy) of every output."""
-    dp = DevicePath(wl, device, flags=flags, backward=backward)
+    dp = DevicePath(wl, device, flags=flags, backward=backward, softmax_scale=softmax_scale)
     dp.fwd()
     dp.merge()
     if backward:

@@ -172,6 +172,28 @@ def test_repeated_calls_reuse_the_workspace():
     _check("o", outs[-1][0][: o_ref.shape[0]], o_ref)
 
 
+@pytest.mark.parametrize("scale", [0.5, 1.0])
+def test_peaked_softmax_large_logits(scale):
+    """A softmax scale far above 1/sqrt(d): scores of std 5.7 / 11.3 (8 / 16 in the kernels' log2 domain), so the
+    running maximum moves by much more than the slack the forward tolerates before it rescales, rows are nearly
+    one-hot, and exp2 runs over its whole range.  Forward, merge of partials with very different LSE, backward."""
+    wl = workloads.custom_workload([700, 333, 129], 128, 1, 2, 4, 2, 128, seed=55, name=f"peaked-scale{scale}")
+    _say(f"case {wl.name}")
+    res = run_path(wl, torch.device("cuda:0"), backward=True, flags=F32, softmax_scale=scale)
+    q, k, v = wl.q(), wl.k(), wl.v()
+    o_ref, lse_ref = orc.worker_fwd(q, k, v, wl.seq_lens, wl.block_size, wl.causal, None, scale)
+    _check("o", res["o"], o_ref)
+    # LSE values reach the hundreds here: the bar is relative to their size (fp32 has 24 bits)
+    fin = np.isfinite(lse_ref)
+    err = np.max(np.abs(res["lse"][fin] - lse_ref[fin]) / np.maximum(1.0, np.abs(lse_ref[fin])))
+    _say(f"  lse: max relative error {err:.3e}")
+    assert err <= TOL_LSE
+    dq, dk, dv = orc.worker_bwd(q, k, v, wl.d_o(), wl.seq_lens, wl.block_size, wl.causal, None, scale)
+    # gradients scale with the softmax scale (dS is multiplied by it): same relative bars
+    for name, ref in (("dq", dq), ("dk", dk), ("dv", dv)):
+        _check(name, res[name], ref, tol_abs=TOL_ABS * max(1.0, scale * np.sqrt(wl.head_dim)), tol_rel=TOL_REL)
+
+
 PART_BF16 = 4   # FCP_FLAG_PART_BF16
 
 
