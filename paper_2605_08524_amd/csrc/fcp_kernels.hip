@@ -524,13 +524,21 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
       const int64_t off = row * q_row_stride + (int64_t)head * D;
       if (to_final ? !a.o_is_f32 : a.part_is_bf16) {
+        // A lane holds columns 8 q4 + 4 g .. + 3 of its row, its partner (lane ^ 32, same row) the other four of
+        // every group of eight.  The two trade halves so that each stores 16 contiguous bytes (8 columns):
+        // the lower lane keeps the even groups, the upper lane the odd ones.
         uint16_t* op = reinterpret_cast<uint16_t*>(to_final ? a.o : a.o_part) + off;
 #pragma unroll
         for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-          for (int q4 = 0; q4 < 4; q4++) {
-            u32x2 h = {pack_bf16(o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv), pack_bf16(o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv)};
-            *reinterpret_cast<u32x2*>(op + dt * 32 + 8 * q4 + 4 * g) = h;
+          for (int m = 0; m < 2; m++) {
+            const uint32_t e0 = pack_bf16(o[dt][8 * m] * inv, o[dt][8 * m + 1] * inv), e1 = pack_bf16(o[dt][8 * m + 2] * inv, o[dt][8 * m + 3] * inv);
+            const uint32_t f0 = pack_bf16(o[dt][8 * m + 4] * inv, o[dt][8 * m + 5] * inv), f1 = pack_bf16(o[dt][8 * m + 6] * inv, o[dt][8 * m + 7] * inv);
+            // swap(x, y): lanes 32-63 of x trade places with lanes 0-31 of y
+            const u32x2 r = __builtin_amdgcn_permlane32_swap(e0, f0, false, false);
+            const u32x2 t = __builtin_amdgcn_permlane32_swap(e1, f1, false, false);
+            const u32x4 h = {r[0], t[0], r[1], t[1]};
+            *reinterpret_cast<u32x4*>(op + dt * 32 + 16 * m + 8 * g) = h;
           }
       } else {
         float* op = reinterpret_cast<float*>(to_final ? a.o : a.o_part) + off;
