@@ -2,8 +2,8 @@
 """Benchmark of the block-attention hot path on one MI355X.
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM:
-forward partials (fcp_block_attn_fwd) -> merge (fcp_merge_partials) -> backward preprocess
-(fcp_bwd_preprocess) -> dK/dV (fcp_block_attn_bwd_dkdv) -> dQ (fcp_block_attn_bwd_dq).  The default workload is the
+forward partials (fcp_block_attn_fwd_out) -> merge (fcp_merge_partials) -> dQ, which also computes D = rowsum(dO o O)
+(fcp_block_attn_bwd_dq_d) -> dK/dV (fcp_block_attn_bwd_dkdv); the last two are what fcp_block_attn_bwd runs.  The default workload is the
 packed variable-length training step (64K tokens, 1024-token blocks, GQA 32/8, d = 128, bf16).
 
 Prints ONE JSON line: whole-step throughput in causal-adjusted TFLOP/s, the roofline of the
@@ -27,9 +27,9 @@ PEAK_HBM_GBS = 8000.0
 # plain copy of known size in the same runs (profiles/cfg5_training_step_hbm_traffic.txt); None
 # for a workload or kernel that has not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.805e9,
-    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.459e9,
-    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 3.220e9,
+    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.768e9,
+    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.417e9,
+    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 4.391e9,
 }
 
 
@@ -98,7 +98,7 @@ def sweep(args):
             wl.block_size, wl.coalesce = bs, c
             dp = DevicePath(wl, dev, flags=FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_O_F32, backward=True, stream=stream)
             f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
-            stages = [dp.fwd, dp.merge, dp.bwd_pre, dp.bwd_dkdv, dp.bwd_dq]
+            stages = [dp.fwd, dp.merge, dp.bwd_dq_d, dp.bwd_dkdv]
             for _ in range(args.warmup):
                 for fn in stages:
                     fn()
@@ -114,7 +114,7 @@ def sweep(args):
             step_ms = sum(ms)
             print(json.dumps({
                 "block_size": bs, "coalesce": c, "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
-                "nnz_per_head": nnz, "ms": {k: round(v, 3) for k, v in zip(("fwd", "merge", "bwd_pre", "bwd_dkdv", "bwd_dq"), ms)},
+                "nnz_per_head": nnz, "ms": {k: round(v, 3) for k, v in zip(("fwd", "merge", "bwd_dq", "bwd_dkdv"), ms)},
                 "ms_per_step": round(step_ms, 3), "tflops": round((f_fwd + f_bwd) / step_ms / 1e9, 1),
                 "fwd_tflops": round(f_fwd / (ms[0] + ms[1]) / 1e9, 1)}), flush=True)
             del dp
@@ -188,7 +188,7 @@ def distribute(args):
     dp = DevicePath(wl, dev, flags=fcp.FCP_FLAG_DIRECT_SINGLE | fcp.FCP_FLAG_O_F32, backward=True, stream=stream)
     f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
     assert nnz == int(w_c[heavy])
-    stages = [dp.fwd, dp.merge, dp.bwd_pre, dp.bwd_dkdv, dp.bwd_dq]
+    stages = [dp.fwd, dp.merge, dp.bwd_dq_d, dp.bwd_dkdv]
     for _ in range(args.warmup):
         for fn in stages:
             fn()
@@ -258,7 +258,7 @@ def main():
 
     stages = [("fwd", dp.fwd), ("merge", dp.merge)]
     if backward:
-        stages += [("bwd_pre", dp.bwd_pre), ("bwd_dkdv", dp.bwd_dkdv), ("bwd_dq", dp.bwd_dq)]
+        stages += [("bwd_dq", dp.bwd_dq_d), ("bwd_dkdv", dp.bwd_dkdv)]
 
     def step(events=None):
         for i, (_, fn) in enumerate(stages):
@@ -291,7 +291,7 @@ def main():
     for i, (name, _) in enumerate(stages):
         stage_ms[name] = sum(evs[s][i][0].elapsed_time(evs[s][i][1]) for s in range(args.steps)) / args.steps
 
-    # Each timed stage except bwd_pre is exactly one kernel launch.  Algorithmic FLOPs per launch:
+    # Each timed stage is exactly one kernel launch.  Algorithmic FLOPs per launch:
     # forward 2 contractions (4 d per unmasked entry and head), dK/dV kernel 4 (S, dP, dV, dK: 8 d),
     # dQ kernel 3 (S, dP, dQ: 6 d; S and dP are recomputed there instead of accumulating dQ with
     # atomics, so the backward executes 14 d per entry for an algorithmic 10 d).

@@ -193,8 +193,8 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
  *                          ([Hq,T_q] fp32 each) in the workspace.
  * fcp_block_attn_bwd_dkdv: KV-stationary kernel, writes dk and dv.
  * fcp_block_attn_bwd_dq:   query-stationary kernel, writes dq.
- * The last two need fcp_bwd_preprocess to have run on the same workspace (same stream, or ordered
- * after it) with the same o / lse / d_o, and are independent of each other.
+ * The last two need fcp_bwd_preprocess (or, for fcp_block_attn_bwd_dkdv, fcp_block_attn_bwd_dq_d) to have run on
+ * the same workspace (same stream, or ordered after it) with the same o / lse / d_o, and are independent of each other.
  * Arguments, layouts and errors as for fcp_block_attn_bwd.
  */
 int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const float* lse, const void* d_o,
@@ -203,6 +203,17 @@ int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, 
                             const void* d_o, float* dk, float* dv, void* workspace, void* stream);
 int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
                           const void* d_o, float* dq, void* workspace, void* stream);
+
+/*
+ * fcp_block_attn_bwd_dq_d -- fcp_block_attn_bwd_dq that needs no fcp_bwd_preprocess: the kernel computes
+ * D = rowsum(dO o O) for the rows of each work item itself (it holds their dO already) and leaves scale*D and
+ * log2(e)*LSE in the workspace, where a later fcp_block_attn_bwd_dkdv on the same workspace finds them.
+ * fcp_block_attn_bwd = this call followed by fcp_block_attn_bwd_dkdv.
+ * o / lse: the forward's final outputs, as for fcp_block_attn_bwd.
+ */
+int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, const void* k, const void* v,
+                            const void* o, const float* lse, const void* d_o, float* dq,
+                            void* workspace, void* stream);
 
 /* Text of the calling thread's last error ("" if none).  The pointer stays valid until the
  * thread's next failing call. */

@@ -744,6 +744,8 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32,
 struct BwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse2; const float* dls;     // head-major [Hq][T_q]: LSE*log2(e) (+inf for empty rows), D*scale
+  // dq_kernel<D, true> computes those two itself from O, LSE and dO and writes them for dkdv_kernel
+  const void* o; const float* lse; int32_t o_is_f32; float* lse2_out; float* dls_out;
   float* dq; float* dk; float* dv;
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
   int64_t t_q;
@@ -1114,7 +1116,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 // K rows past a ragged end are zero in LDS, so their dS contributes nothing: only the
 // diagonal needs a mask.  Every dQ row has one writer: plain stores, deterministic.
 // =====================================================================================
-template <int D>
+template <int D, bool WITH_D>
 __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
@@ -1178,7 +1180,45 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
         }
         qf[kc] = as_bf16x8(zq); dof[kc] = as_bf16x8(zd);
       }
-      if (row_ok) {
+      if constexpr (WITH_D) {
+        // D = rowsum(dO o O) of this lane's row: its 8 columns of every k-chunk, plus the partner lane's
+        // (lane ^ 32, same row, the other 8).  The backward preprocess pass is then not needed: the two
+        // per-row scalars are written here, head-major, for the dK/dV kernel that runs afterwards.
+        float part = 0.f;
+        if (row_ok) {
+#pragma unroll
+          for (int kc = 0; kc < KC; kc++) {
+            float ov[8];
+            if (a.o_is_f32) {
+              const float* op = reinterpret_cast<const float*>(a.o) + off + kc * 16;
+              const f32x4 x0 = *reinterpret_cast<const f32x4*>(op), x1 = *reinterpret_cast<const f32x4*>(op + 4);
+#pragma unroll
+              for (int i = 0; i < 4; i++) { ov[i] = x0[i]; ov[4 + i] = x1[i]; }
+            } else {
+              const u32x4 x = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(a.o) + off + kc * 16);
+#pragma unroll
+              for (int i = 0; i < 4; i++) { ov[2 * i] = __uint_as_float(x[i] << 16); ov[2 * i + 1] = __uint_as_float(x[i] & 0xffff0000u); }
+            }
+            const u32x4 dv = __builtin_bit_cast(u32x4, dof[kc]);
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+              part += __uint_as_float(dv[i] << 16) * ov[2 * i];
+              part += __uint_as_float(dv[i] & 0xffff0000u) * ov[2 * i + 1];
+            }
+          }
+        }
+        const float d_row = part + xor32(part);
+        if (row_ok) {
+          const float l = a.lse[(int64_t)(q_start + my_row) * a.n_q_heads + head];
+          lse_l = (l == -INFINITY) ? INFINITY : l * kLog2e;
+          dl_l = d_row * a.scale;
+          if (g == 0) {
+            const int64_t hr = (int64_t)head * a.t_q + q_start + my_row;
+            a.lse2_out[hr] = lse_l;
+            a.dls_out[hr] = dl_l;
+          }
+        }
+      } else if (row_ok) {
         const int64_t hr = (int64_t)head * a.t_q + q_start + my_row;
         lse_l = a.lse2[hr];
         dl_l = a.dls[hr];
@@ -1411,6 +1451,7 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
   a->n_q_heads = p->n_q_heads; a->n_kv_heads = p->n_kv_heads;
   a->scale = resolve_scale(p); a->scale_log2 = a->scale * kLog2e;
   a->dq = nullptr; a->dk = nullptr; a->dv = nullptr;
+  a->o = nullptr; a->lse = nullptr; a->o_is_f32 = 0; a->lse2_out = nullptr; a->dls_out = nullptr;
   return FCP_OK;
 }
 
@@ -1430,20 +1471,48 @@ extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, cons
   return check_launch("fcp_block_attn_bwd_dkdv");
 }
 
-extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                     const void* d_o, float* dq, void* workspace, void* stream) {
+// o / lse == NULL: the per-row scalars come from fcp_bwd_preprocess; else the kernel computes and publishes them.
+static int launch_dq(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,
+                     const void* o, const float* lse, const void* d_o, float* dq, void* workspace, void* stream) {
   WsLayout L;
   BwdArgs a;
   int rc = fill_bwd_args(p, &L, &a, workspace);
   if (rc) return rc;
   if (L.n_dq_items == 0) return FCP_OK;
-  if (!q || !k || !v || !d_o || !dq || !workspace) { set_error("fcp_block_attn_bwd_dq: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !d_o || !dq || !workspace) { set_error("%s: NULL pointer", who); return FCP_ERR_INVALID_ARG; }
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dq = dq;
   const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(dq_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(dq_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  return check_launch("fcp_block_attn_bwd_dq");
+  const bool with_d = o != nullptr;
+  if (with_d) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    a.o = o; a.lse = lse; a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
+    a.dls_out = reinterpret_cast<float*>(ws + L.off_dls);
+    a.lse2_out = reinterpret_cast<float*>(ws + L.off_lse2);
+    if (p->head_dim == 128) hipLaunchKernelGGL((dq_kernel<128, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((dq_kernel<64, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  } else {
+    if (p->head_dim == 128) hipLaunchKernelGGL((dq_kernel<128, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((dq_kernel<64, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  }
+  return check_launch(who);
+}
+
+extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                     const void* d_o, float* dq, void* workspace, void* stream) {
+  return launch_dq("fcp_block_attn_bwd_dq", p, q, k, v, nullptr, nullptr, d_o, dq, workspace, stream);
+}
+
+extern "C" int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                       const void* o, const float* lse, const void* d_o, float* dq,
+                                       void* workspace, void* stream) {
+  if (!o || !lse) {
+    int rc = validate_problem(p);
+    if (rc) return rc;
+    set_error("fcp_block_attn_bwd_dq_d: NULL pointer");
+    return FCP_ERR_INVALID_ARG;
+  }
+  return launch_dq("fcp_block_attn_bwd_dq_d", p, q, k, v, o, lse, d_o, dq, workspace, stream);
 }
 
 extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
@@ -1455,10 +1524,9 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
     set_error("fcp_block_attn_bwd: NULL pointer");
     return FCP_ERR_INVALID_ARG;
   }
-  int rc = fcp_bwd_preprocess(p, o, lse, d_o, workspace, stream);
+  // dQ first: its kernel also leaves the per-row scalars (D * scale, LSE * log2 e) that dK/dV needs
+  int rc = fcp_block_attn_bwd_dq_d(p, q, k, v, o, lse, d_o, dq, workspace, stream);
   if (rc) return rc;
-  rc = fcp_block_attn_bwd_dkdv(p, q, k, v, d_o, dk, dv, workspace, stream);
-  if (rc) return rc;
-  return fcp_block_attn_bwd_dq(p, q, k, v, d_o, dq, workspace, stream);
+  return fcp_block_attn_bwd_dkdv(p, q, k, v, d_o, dk, dv, workspace, stream);
 }
 

@@ -71,6 +71,10 @@ class DevicePath:
     def bwd_pre(self):
         B.fcp_bwd_preprocess(self.problem, self.o, self.lse, self.d_o, self.ws_ptr, self.stream)
 
+    def bwd_dq_d(self):
+        B.fcp_block_attn_bwd_dq_d(self.problem, self.q, self.k, self.v, self.o, self.lse, self.d_o,
+                                  self.dq, self.ws_ptr, self.stream)
+
     def bwd_dkdv(self):
         B.fcp_block_attn_bwd_dkdv(self.problem, self.q, self.k, self.v, self.d_o,
                                   self.dk, self.dv, self.ws_ptr, self.stream)

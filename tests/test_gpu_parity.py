@@ -194,6 +194,34 @@ def test_peaked_softmax_large_logits(scale):
         _check(name, res[name], ref, tol_abs=TOL_ABS * max(1.0, scale * np.sqrt(wl.head_dim)), tol_rel=TOL_REL)
 
 
+@pytest.mark.parametrize("f32", [0, 1])
+def test_backward_stage_entry_points_agree(f32):
+    """fcp_block_attn_bwd (dQ kernel with D fused in, then dK/dV) against the three stand-alone stages
+    (preprocess, dK/dV, dQ): same gradients up to the summation order of D.  The fused variant runs first, on a
+    workspace whose per-row scalars are still zero, so a dQ kernel that did not publish them would show in dK / dV."""
+    from paper_2605_08524_amd.harness import DevicePath
+    dev = torch.device("cuda:0")
+    wl = workloads.custom_workload([900, 50, 1300], 128, 1, 4, 8, 2, 128, seed=61, name="stages")
+    _say(f"case {wl.name} f32={f32}")
+    dp = DevicePath(wl, dev, flags=F32 if f32 else 0, backward=True)
+    dp.fwd(); dp.merge()
+    res = {}
+    for name, calls in (("fused", (dp.bwd_dq_d, dp.bwd_dkdv)), ("staged", (dp.bwd_pre, dp.bwd_dkdv, dp.bwd_dq)), ("one call", (dp.bwd,))):
+        for t in (dp.dq, dp.dk, dp.dv):
+            t.fill_(float("nan"))
+        for fn in calls:
+            fn()
+        torch.cuda.synchronize(dev)
+        res[name] = [t.cpu().numpy().copy() for t in (dp.dq, dp.dk, dp.dv)]
+    for x, y in zip(res["fused"], res["one call"]):
+        assert np.array_equal(x, y)
+    for nm, x, y in zip(("dq", "dk", "dv"), res["fused"], res["staged"]):
+        assert np.isfinite(x).all() and np.isfinite(y).all()
+        err = float(np.max(np.abs(x - y)))
+        _say(f"  {nm}: fused vs staged max-abs {err:.3e}")
+        assert err <= 2e-3
+
+
 PART_BF16 = 4   # FCP_FLAG_PART_BF16
 
 
