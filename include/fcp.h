@@ -188,7 +188,8 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
                        float* dq, float* dk, float* dv, void* workspace, void* stream);
 
 /*
- * The three stages of fcp_block_attn_bwd, exported so that a caller can time or overlap them.
+ * The stages of the backward as separate calls, so that a caller can time or overlap them.  fcp_block_attn_bwd
+ * itself runs fcp_block_attn_bwd_dq_d (below) followed by fcp_block_attn_bwd_dkdv.
  * fcp_bwd_preprocess:      computes D = rowsum(dO o O) and leaves scale*D and log2(e)*LSE
  *                          ([Hq,T_q] fp32 each) in the workspace.
  * fcp_block_attn_bwd_dkdv: KV-stationary kernel, writes dk and dv.
