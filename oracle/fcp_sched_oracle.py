@@ -10,8 +10,8 @@ What it follows (all from the paper):
 * Block costs (appendix "Block Assignment Algorithm", first paragraph): every block i
   has a memory usage m_i and a compute amount c_i.  Read here as m_i = tokens of the
   block, c_i = number of unmasked (query row, key column) score entries of the block's
-  query rows, per head; the paper gives no formula ("estimated from the context length
-  of the source sequence").
+  query rows, per head; the paper gives no formula (it only says that both are estimated
+  from the length of the sequence the block comes from).
 * Short sequences (section "Block Distributor", sharding policy) are packed into shared units by
   first-fit decreasing; the paper asks for as few blocks as possible and names no rule.
 * Greedy Load-Balanced Assignment (appendix algorithm of that name): average loads,
