@@ -1186,24 +1186,38 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
         // per-row scalars are written here, head-major, for the dK/dV kernel that runs afterwards.
         float part = 0.f;
         if (row_ok) {
-#pragma unroll
-          for (int kc = 0; kc < KC; kc++) {
-            float ov[8];
-            if (a.o_is_f32) {
-              const float* op = reinterpret_cast<const float*>(a.o) + off + kc * 16;
-              const f32x4 x0 = *reinterpret_cast<const f32x4*>(op), x1 = *reinterpret_cast<const f32x4*>(op + 4);
-#pragma unroll
-              for (int i = 0; i < 4; i++) { ov[i] = x0[i]; ov[4 + i] = x1[i]; }
-            } else {
-              const u32x4 x = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(a.o) + off + kc * 16);
-#pragma unroll
-              for (int i = 0; i < 4; i++) { ov[2 * i] = __uint_as_float(x[i] << 16); ov[2 * i + 1] = __uint_as_float(x[i] & 0xffff0000u); }
-            }
-            const u32x4 dv = __builtin_bit_cast(u32x4, dof[kc]);
+          // all loads of the row first, then the arithmetic: one round trip to memory, not one per k-chunk
+          auto dot8 = [&](const u32x4 dv, const float (&ov)[8]) {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
               part += __uint_as_float(dv[i] << 16) * ov[2 * i];
               part += __uint_as_float(dv[i] & 0xffff0000u) * ov[2 * i + 1];
+            }
+          };
+          if (a.o_is_f32) {
+            const float* op = reinterpret_cast<const float*>(a.o) + off;
+            f32x4 x[2 * KC];
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) {
+              x[2 * kc] = *reinterpret_cast<const f32x4*>(op + kc * 16);
+              x[2 * kc + 1] = *reinterpret_cast<const f32x4*>(op + kc * 16 + 4);
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) {
+              const float ov[8] = {x[2 * kc][0], x[2 * kc][1], x[2 * kc][2], x[2 * kc][3], x[2 * kc + 1][0], x[2 * kc + 1][1], x[2 * kc + 1][2], x[2 * kc + 1][3]};
+              dot8(__builtin_bit_cast(u32x4, dof[kc]), ov);
+            }
+          } else {
+            const uint16_t* op = reinterpret_cast<const uint16_t*>(a.o) + off;
+            u32x4 x[KC];
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) x[kc] = *reinterpret_cast<const u32x4*>(op + kc * 16);
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) {
+              float ov[8];
+#pragma unroll
+              for (int i = 0; i < 4; i++) { ov[2 * i] = __uint_as_float(x[kc][i] << 16); ov[2 * i + 1] = __uint_as_float(x[kc][i] & 0xffff0000u); }
+              dot8(__builtin_bit_cast(u32x4, dof[kc]), ov);
             }
           }
         }
