@@ -217,6 +217,8 @@ def main():
     ap.add_argument("--two-step", action="store_true",
                     help="every query block goes through the partial buffers and the merge, also those with one slot")
     ap.add_argument("--bf16-partials", action="store_true", help="keep the partial O buffer in bf16 (FCP_FLAG_PART_BF16)")
+    ap.add_argument("--heads", default=None, metavar="HQ/HKV",
+                    help="override the head counts of the workload, e.g. 64/8 (the head shape of the paper's model)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
@@ -243,6 +245,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = workloads.make_workload(args.config, args.seed)
+    if args.heads:
+        wl.n_q_heads, wl.n_kv_heads = (int(x) for x in args.heads.split("/"))
+        wl.name += f"-heads{wl.n_q_heads}x{wl.n_kv_heads}"
     backward = args.config == 5
     stream = torch.cuda.current_stream(dev)
     t0 = time.perf_counter()
