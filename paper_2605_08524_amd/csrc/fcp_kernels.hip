@@ -1248,8 +1248,12 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
     ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
     auto dma = [&](int b) {
       const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
-      tile_dma<D, kFwdTileN, 8>(lds_kv[b], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
-      tile_dma<D, kFwdTileN, 8>(lds_kv[b] + TB, vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      // Only the waves of sub-item 0 load: they reach every tile barrier well before the others (the SIMD
+      // favours the wave that was started first), so the loads cost them nothing and relieve the slower four.
+      if (sub == 0) {
+        tile_dma<D, kFwdTileN, 4>(lds_kv[b], kbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+        tile_dma<D, kFwdTileN, 4>(lds_kv[b] + TB, vbase + row0, kv_row_stride, ti.cur.kv_len - ti.c0, zeros, wave, lane, dma_off);
+      }
     };
     DevPair tp = ti.cur;
     int tc0 = 0;
