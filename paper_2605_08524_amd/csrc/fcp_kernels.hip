@@ -714,29 +714,31 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32,
 
 // =====================================================================================
 // Backward, part 1 -- dK and dV.  Item = (KV tile of 128 rows, KV head); workgroup of 8 waves, two
-// per SIMD.  KV rows 32*s .. +32 of the tile (s = wave % 4) are handled by a producer wave (s) and
-// a consumer wave (s + 4) that share a SIMD.  A step is 32 query rows of one head:
-//   producer  A(t): S = Q K^T, dP = dO V^T      (A operands: row-wise reads of the Q / dO tiles in
+// per SIMD: four producers and four consumers.  A step is 32 query rows of one head:
+//   producer s, KV rows 32*s .. +32 of the tile:
+//             A(t): S = Q K^T, dP = dO V^T      (A operands: row-wise reads of the Q / dO tiles in
 //                                                LDS; B operands: the wave's K / V rows in registers)
 //             B(t): P = exp2(S*c - LSE*log2e), masked on the diagonal; dS = P o (dP*scale - D*scale);
-//                   P and dS go to the consumer as bf16 MFMA B operands through LDS
-//   consumer  C(t): dV^T += dO^T P, dK^T += Q^T dS   (A operands: transpose reads of the same tiles)
-// dK^T / dV^T (rows = d, cols = KV rows) stay in the consumer's accumulators across every dependent
-// query block and the G query heads of the group, so each dK / dV row has exactly one writer.
+//                   P and dS go to the consumers as bf16 MFMA B operands through LDS
+//   consumer c, d rows 32*c .. +32 of dK^T / dV^T for all 128 KV rows (d = 64: 32 d rows x 64 KV rows):
+//             C(t): dV^T += dO^T P, dK^T += Q^T dS   (A operands: transpose reads of its d rows of the
+//                   same tiles, each used for every 32-row KV group; B operands: every producer's P / dS)
+// dK^T / dV^T (rows = d, cols = KV rows) stay in the consumers' accumulators across every dependent
+// query block and the G query heads of the group, so each dK / dV element has exactly one writer.
 // The roles are decoupled by whole steps: in one barrier interval the consumer runs C(t) while
 // the producer issues the MFMAs of A(t+2) with the vector work B(t+1) interleaved between them by
 // hand.  The vector ALU work of the SIMD thus sits in one wave and half of its MFMAs in the
 // other, and neither wave waits for the other inside an interval.  Q / dO tiles and the per-row
 // scalars sit in a ring of seven LDS buffers filled by LDS-DMA (issued by the consumers) six
 // steps ahead of their C phase; a tile is in place two intervals before the producer reads it,
-// so both roles request the first LDS operands of an interval before the barrier that opens it.
+// so the producer requests its first LDS operands of an interval, and the consumer all its A
+// operands, before the barrier that opens it.
 // One workgroup barrier per step.  Steps before the first and past the last of an item run on
 // +inf LSE (P = dS = 0), which keeps the instruction stream and the count of loads in flight
 // identical for every step; the ring runs on from item to item.
-// The kernel is bound by LDS time, not by the matrix pipe: per step and SIMD pair the LDS serves
-// 16 row reads + 8 scalar reads (b128, 256 B/clk), 32 transpose reads (b64, 160 B/clk), the
-// 8 KB hand-over and the 4 KB of DMA writes (writes: 76 B/clk), about 1.25x the 1024 cycles of
-// the 32 MFMAs (rates measured on this chip).
+// LDS time per step and SIMD pair: 16 row reads + 8 scalar reads + 16 hand-over reads (b128,
+// 256 B/clk), 8 transpose reads (b64, 160 B/clk), the 8 KB hand-over and the 4 KB of DMA writes
+// (writes: 76 B/clk), about 1.15x the 1024 cycles of the 32 MFMAs (rates measured on this chip).
 // dQ is not produced here: accumulating it across KV tiles needs fp32 atomics, and the chip
 // sustains only about 1.35 TB/s of them (measured), several times below what this kernel would
 // emit.  dq_kernel below recomputes S and dP query-stationary instead.
@@ -865,13 +867,13 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       const float* sc_arr = (g ? a.dls : a.lse2) + l32;
       const float* sc_page = (g ? reinterpret_cast<const float*>(zeros) : infs) + l32;
       const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      uint32_t tr_lo[DT], tr_hi[DT];       // transpose-read addresses inside a step buffer (Q tile; dO is +TB)
-#pragma unroll
-      for (int dt = 0; dt < DT; dt++) {
-        tr_lo[dt] = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-        tr_hi[dt] = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
-      }
-      f32x16 acc_k[DT], acc_v[DT];     // dK^T, dV^T: rows = d, cols = this pair's KV rows
+      // This wave owns d rows 32*cdt .. +31 of dK^T / dV^T for NN of the tile's 32-row KV groups.
+      constexpr int NN = DT;
+      const int cdt = sub % DT, n0 = (sub / DT) * NN;
+      uint32_t tr_lo1 = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row, 4 * cdt + (tr_col >> 3)) + (tr_col & 4) * 2;
+      uint32_t tr_hi1 = lds_addr(lds_t[0]) + b_c * BUF + tile_off<D>(4 * g + tr_row + 8, 4 * cdt + (tr_col >> 3)) + (tr_col & 4) * 2;
+      const uint32_t hsrc = lds_addr(lds_h[0][0]) + n0 * 4096 + lane * 16;
+      f32x16 acc_k[DT], acc_v[DT];     // dK^T, dV^T: rows = d, cols = KV rows
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -927,61 +929,65 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       describe();          // tile 4, requested inside the first interval
       dma_wait();
       __syncthreads();
-      u32x4 op[PFC];        // transposed operands, requested PFC MFMAs ahead (across the barrier too)
-      auto fetch = [&](int u) {
-        // operand u of C: j = k-chunk (16 query rows), w = 0: dO^T x P (dV), 1: Q^T x dS (dK)
-        const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
-        const uint32_t o = 16 * j * (D * 2) + (w == 0 ? TB : 0);
-        return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo[dt] + o, tr_hi[dt] + o));
+      // A operands of a step: (k-chunk j of 16 query rows, w = 0: dO^T for dV, 1: Q^T for dK), index 2j + w.
+      // Each serves the NN MFMAs of its KV groups; the B operands (P / dS of every group) stream from the
+      // hand-over buffers, PFC MFMAs ahead.  While interval i runs, the A operands of step i+1 are fetched
+      // from the next tile as soon as their registers are free.
+      auto fetch_a = [&](int jw) {
+        const uint32_t o = 16 * (jw >> 1) * (D * 2) + ((jw & 1) == 0 ? TB : 0);
+        return __builtin_bit_cast(u32x4, lds_tr_pair_at(tr_lo1 + o, tr_hi1 + o));
       };
+      auto next_tile = [&]() {
+        const int st = (b_c == NB - 1) ? -(NB - 1) * BUF : BUF;
+        tr_lo1 += st; tr_hi1 += st;
+        b_c = (b_c == NB - 1) ? 0 : b_c + 1;
+      };
+      u32x4 aop[4];
 #pragma unroll
-      for (int u = 0; u < PFC; u++) op[u] = fetch(u);
-
+      for (int jw = 0; jw < 4; jw++) aop[jw] = fetch_a(jw);
+      next_tile();
       for (int iv = 0; iv < n_iv; iv++) {
-        // B operands of C(i): P (k-chunks 0, 1) and dS (k-chunks 0, 1) as left by the producer
-        u32x4 bop[4];
+        const uint32_t hb_src = hsrc + hb * (4 * 4096);
+        // MFMA u = (2j + w) * NN + n reads operand (w ? 2 : 0) + j of KV group n0 + n
+        auto fetch_b = [&](int u) {
+          const int jw = u / NN, n = u % NN;
+          return lds_read16(hb_src + n * 4096 + (((jw & 1) ? 2 : 0) + (jw >> 1)) * 1024);
+        };
+        u32x4 bop[PFC];
 #pragma unroll
-        for (int o = 0; o < 4; o++) bop[o] = lds_read16(lds_h0 + hb * (4 * 4096) + o * 1024);
+        for (int u = 0; u < PFC; u++) bop[u] = fetch_b(u);
 #pragma unroll
         for (int u = 0; u < NS; u++) {
-          const int j = u / (2 * DT), w = (u / DT) & 1, dt = u % DT;
-          if (w == 0) acc_v[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PFC]), as_bf16x8(bop[j]), acc_v[dt], 0, 0, 0);
-          else acc_k[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PFC]), as_bf16x8(bop[2 + j]), acc_k[dt], 0, 0, 0);
-          if (u == NS - PFC) {
-            // the last operand of this tile has been requested: move on to the next tile
-            const int st = (b_c == NB - 1) ? -(NB - 1) * BUF : BUF;
-#pragma unroll
-            for (int dt2 = 0; dt2 < DT; dt2++) { tr_lo[dt2] += st; tr_hi[dt2] += st; }
-            b_c = (b_c == NB - 1) ? 0 : b_c + 1;
-          }
-          op[u % PFC] = fetch((u + PFC) % NS);
+          const int jw = u / NN, n = u % NN;
+          if ((jw & 1) == 0) acc_v[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aop[jw]), as_bf16x8(bop[u % PFC]), acc_v[n], 0, 0, 0);
+          else acc_k[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(aop[jw]), as_bf16x8(bop[u % PFC]), acc_k[n], 0, 0, 0);
+          if (u + PFC < NS) bop[u % PFC] = fetch_b(u + PFC);
+          if (n == NN - 1) aop[jw] = fetch_a(jw);
           if (u == NS / 2) issue();
           __builtin_amdgcn_sched_barrier(0);
         }
-        // the tiles of step i+4 have landed once at most two steps' loads are in flight
+        next_tile();
         __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * DMA_PER_STEP) & 15) | (((2 * DMA_PER_STEP) >> 4) << 14));
-        // A bare barrier: __syncthreads() would first wait for every LDS operation of this wave,
-        // i.e. for the operands of the next interval that were just requested (about 200 cycles on
-        // the wave that already is the slower one).  Nothing this wave wrote needs publishing: its
-        // DMA loads have landed (vmcnt above), and the operands it read have been consumed by MFMAs.
         asm volatile("s_barrier" ::: "memory");
         describe();
         hb ^= 1;
       }
-      dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
-
-      // ---- epilogue: the only writer of these dK / dV rows
-      if (kv_ok) {
-        const int64_t off = (int64_t)(it.kv_start + my_kv) * kv_row_stride + (int64_t)it.kv_head * D;
+      b_c = (b_c == 0) ? NB - 1 : b_c - 1;     // the tile looked ahead to belongs to the next item's first interval
+      dma_wait();
+      // ---- epilogue: the only writer of these dK / dV elements
 #pragma unroll
-        for (int dt = 0; dt < DT; dt++)
+      for (int n = 0; n < NN; n++) {
+        const int kv_r = (n0 + n) * 32 + l32;
+        if (kv_r < it.kv_rows) {
+          const int64_t off = (int64_t)(it.kv_start + kv_r) * kv_row_stride + (int64_t)it.kv_head * D + cdt * 32 + 4 * g;
 #pragma unroll
           for (int q4 = 0; q4 < 4; q4++) {
-            f32x4 wk = {acc_k[dt][4 * q4], acc_k[dt][4 * q4 + 1], acc_k[dt][4 * q4 + 2], acc_k[dt][4 * q4 + 3]};
-            f32x4 wv = {acc_v[dt][4 * q4], acc_v[dt][4 * q4 + 1], acc_v[dt][4 * q4 + 2], acc_v[dt][4 * q4 + 3]};
-            *reinterpret_cast<f32x4*>(a.dk + off + dt * 32 + 8 * q4 + 4 * g) = wk;
-            *reinterpret_cast<f32x4*>(a.dv + off + dt * 32 + 8 * q4 + 4 * g) = wv;
+            f32x4 wk = {acc_k[n][4 * q4], acc_k[n][4 * q4 + 1], acc_k[n][4 * q4 + 2], acc_k[n][4 * q4 + 3]};
+            f32x4 wv = {acc_v[n][4 * q4], acc_v[n][4 * q4 + 1], acc_v[n][4 * q4 + 2], acc_v[n][4 * q4 + 3]};
+            *reinterpret_cast<f32x4*>(a.dk + off + 8 * q4) = wk;
+            *reinterpret_cast<f32x4*>(a.dv + off + 8 * q4) = wv;
           }
+        }
       }
     } else {
       // =============================== producer ===============================
