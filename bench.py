@@ -206,6 +206,27 @@ def distribute(args):
                       "ms_per_step": round(ms, 3), "tflops": round((f_fwd + f_bwd) / ms / 1e9, 1)}), flush=True)
 
 
+def mfma_sustained(dev, stream):
+    """What the matrix pipes sustain on a pure stream of the kernels' MFMA, by operand values
+    (fcp_mfma_probe): the chip lowers its clock under the power drawn by random operands, so the
+    rate it can hold on real data is well below the published peak that zeros reach."""
+    import torch
+    from paper_2605_08524_amd import fcp_device_info, fcp_mfma_probe
+    n_cu = fcp_device_info()["n_compute_units"]
+    out = torch.zeros(8 * n_cu, dtype=torch.float32, device=dev)
+    res = {}
+    for name, kind in (("zero_operands", 0), ("random_operands", 2)):
+        iters = 60000                                   # 25-40 ms per launch
+        fcp_mfma_probe(kind, iters // 4, out, stream)   # lets the clock settle for this kind of data
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fcp_mfma_probe(kind, iters, out, stream)
+        e1.record(stream)
+        torch.cuda.synchronize(dev)
+        res[name] = round(n_cu * 8 * iters * 16 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -214,6 +235,11 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload: 5 = training step (default), 2/3/4 = forward only")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--inputs", choices=("normal", "zeros", "half"), default="normal",
+                    help="operand values: the workload's N(0,1) tensors (default: the benchmark), or all zeros / all 0.5 "
+                         "(NOT a benchmark number: same instruction stream, shows how much the chip's clock depends on the data)")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the pure-MFMA measurement (sustained rate on zero / random operands) that is reported beside the roofline")
     ap.add_argument("--two-step", action="store_true",
                     help="every query block goes through the partial buffers and the merge, also those with one slot")
     ap.add_argument("--bf16-partials", action="store_true", help="keep the partial O buffer in bf16 (FCP_FLAG_PART_BF16)")
@@ -256,6 +282,9 @@ def main():
     if args.bf16_partials:
         flags |= FCP_FLAG_PART_BF16
     dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream)
+    if args.inputs != "normal":
+        for t in (dp.q, dp.k, dp.v) + ((dp.d_o,) if backward else ()):
+            t.fill_(0.0 if args.inputs == "zeros" else 0.5)
     torch.cuda.synchronize(dev)
     setup_s = time.perf_counter() - t0
     f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
@@ -324,7 +353,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic" if args.inputs == "normal" else f"synthetic, all operands {args.inputs} (clock study, not a benchmark)",
         "config": {
             "workload": wl.name, "seed": args.seed, "tokens_q": p.t_q, "tokens_kv": p.t_kv,
             "block_size": wl.block_size, "coalesce": wl.coalesce, "n_q_heads": wl.n_q_heads,
@@ -347,6 +376,11 @@ def main():
         "grid": info, "setup_s": round(setup_s, 2),
         "host_ms": {"plan_blocks": round(dp.plan_ms, 3), "queue_build": round(dp.queue_build_ms, 3)},
     }
+    if not args.no_mfma_probe:
+        # context for the roofline, measured after the timed region: the published peak stays the denominator of "frac"
+        sus = mfma_sustained(dev, stream)
+        out["mfma_sustained_tflops"] = sus
+        out["roofline"]["frac_of_sustained_random_operands"] = round(achieved / sus["random_operands"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl) if backward else None
     print(json.dumps(out), flush=True)

@@ -31,7 +31,7 @@ EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_block_attn_bwd_dq_d",
-    "fcp_last_error", "fcp_device_info",
+    "fcp_last_error", "fcp_device_info", "fcp_mfma_probe",
     "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
     "fcp_coalesce_stages", "fcp_pack_units",
 )
@@ -90,6 +90,7 @@ def _load():
     lib.fcp_coalesce_stages.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, i32p]
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
+    lib.fcp_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     for name in EXPORTS:
         if name != "fcp_last_error":
             getattr(lib, name).restype = C.c_int
@@ -226,6 +227,11 @@ def fcp_device_info():
     a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
     _check(_lib.fcp_device_info(C.byref(a), C.byref(b), C.byref(c)))
     return dict(n_compute_units=a.value, fwd_grid=b.value, bwd_grid=c.value)
+
+
+def fcp_mfma_probe(operand_kind: int, iters: int, out, stream=None):
+    """Launches the pure-MFMA measurement kernel; the caller times it.  FLOPs = CUs * 8 * iters * 16 * 32768."""
+    _check(_lib.fcp_mfma_probe(int(operand_kind), int(iters), _ptr(out), _stream(stream)))
 
 
 # ---------------------------------------------------------------- host-side scheduling (fcp_sched.h)

@@ -299,3 +299,31 @@ def test_distributed_share_of_the_most_loaded_worker(n_workers):
     wl = workloads.custom_workload(lens, bs, 1, 4, 8, 2, 128, q_owned=owned, seed=77, name=f"share{heavy}of{n_workers}")
     res = _full_parity(wl, backward=True, flags=F32)
     assert res["o"].shape[0] == int(w_m[heavy])
+
+
+def test_mfma_probe_runs_and_random_operands_are_not_faster_than_zeros():
+    """The measurement aid behind the benchmark's sustained-MFMA figures: it must run, leave finite
+    checksums (zeros for zero operands), and the chip must not hold a higher rate on random operands."""
+    import paper_2605_08524_amd as fcp
+    dev = torch.device("cuda:0")
+    n_cu = fcp.fcp_device_info()["n_compute_units"]
+    out = torch.full((8 * n_cu,), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    ms = {}
+    for kind in (0, 2):
+        _say(f"mfma probe kind {kind}")
+        fcp.fcp_mfma_probe(kind, 2000, out, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fcp.fcp_mfma_probe(kind, 8000, out, stream)
+        e1.record(stream)
+        torch.cuda.synchronize(dev)
+        ms[kind] = e0.elapsed_time(e1)
+        assert bool(torch.isfinite(out).all())
+        if kind == 0:
+            assert float(out.abs().max()) == 0.0
+        else:
+            assert float(out.abs().max()) > 0.0
+    tflops = {k: n_cu * 8 * 8000 * 16 * 32768.0 / (v * 1e-3) / 1e12 for k, v in ms.items()}
+    _say(f"pure MFMA stream: zeros {tflops[0]:.0f} TFLOP/s, random {tflops[2]:.0f} TFLOP/s")
+    assert 500 < tflops[2] <= tflops[0] * 1.02 and tflops[0] < 2600

@@ -146,6 +146,13 @@ def test_null_pointers_are_rejected_before_any_launch():
     assert e.value.code == binding.FCP_ERR_INVALID_ARG
 
 
+def test_mfma_probe_rejects_bad_arguments_before_any_launch():
+    for kind, iters, out in ((0, 10, 0), (0, 0, 256), (3, 10, 256), (-1, 10, 256)):
+        with pytest.raises(fcp.FcpError) as e:
+            fcp.fcp_mfma_probe(kind, iters, out)
+        assert e.value.code == binding.FCP_ERR_INVALID_ARG
+
+
 def test_workload_generators_are_seeded():
     a, b = workloads.make_workload(2, 0), workloads.make_workload(2, 0)
     assert np.array_equal(a.seq_lens, b.seq_lens) and a.seq_lens.sum() == 65536
