@@ -59,6 +59,7 @@ enum {
                                     traffic of the partials; LSE partials stay fp32.  Set it for every call on a problem.
                                     A final O merged from bf16 partials carries bf16 rounding whatever its own dtype:
                                     meant for forward-only use (the backward's D = rowsum(dO o O) inherits it). */
+  FCP_FLAG_GRAD_BF16 = 8,        /* the backward writes dq, dk, dv as bf16 instead of fp32 */
   FCP_FLAG_DIRECT_SINGLE = 2     /* a query block with ONE slot needs no reduction: fcp_block_attn_fwd_out writes its
                                     result straight to the final o / lse and fcp_merge_partials leaves it alone.
                                     Set it before fcp_workspace_bytes / fcp_queue_build and keep it for every call
@@ -180,12 +181,13 @@ int fcp_merge_partials(const fcp_problem* p, const void* o_part, const float* ls
  * dS = P o (dP - D); dQ += scale dS K; dK += scale dS^T Q; dK/dV are summed over the query
  * heads of a KV head and hold only the owned query rows' contribution.
  * o: final O as written by fcp_merge_partials (dtype per flags); lse: final LSE; d_o bf16.
- * dq [T_q,Hq,d], dk, dv [T_kv,Hkv,d]: device fp32, fully overwritten; every row has exactly one
- * writer and a fixed summation order, so results are bit-reproducible from run to run.
+ * dq [T_q,Hq,d], dk, dv [T_kv,Hkv,d]: device fp32, or bf16 with FCP_FLAG_GRAD_BF16 (the fp32 sums are
+ * rounded to nearest-even once, in the kernel that holds them: no cast pass); fully overwritten; every
+ * row has exactly one writer and a fixed summation order, so results are bit-reproducible from run to run.
  */
 int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
                        const void* o, const float* lse, const void* d_o,
-                       float* dq, float* dk, float* dv, void* workspace, void* stream);
+                       void* dq, void* dk, void* dv, void* workspace, void* stream);
 
 /*
  * The stages of the backward as separate calls, so that a caller can time or overlap them.  fcp_block_attn_bwd
@@ -201,9 +203,9 @@ int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const
 int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const float* lse, const void* d_o,
                        void* workspace, void* stream);
 int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
-                            const void* d_o, float* dk, float* dv, void* workspace, void* stream);
+                            const void* d_o, void* dk, void* dv, void* workspace, void* stream);
 int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
-                          const void* d_o, float* dq, void* workspace, void* stream);
+                          const void* d_o, void* dq, void* workspace, void* stream);
 
 /*
  * fcp_block_attn_bwd_dq_d -- fcp_block_attn_bwd_dq that needs no fcp_bwd_preprocess: the kernel computes
@@ -213,7 +215,7 @@ int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, co
  * o / lse: the forward's final outputs, as for fcp_block_attn_bwd.
  */
 int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, const void* k, const void* v,
-                            const void* o, const float* lse, const void* d_o, float* dq,
+                            const void* o, const float* lse, const void* d_o, void* dq,
                             void* workspace, void* stream);
 
 /* Text of the calling thread's last error ("" if none).  The pointer stays valid until the

@@ -26,6 +26,7 @@ FCP_KIND_FULL, FCP_KIND_DIAG = 0, 1
 FCP_FLAG_O_F32 = 1
 FCP_FLAG_DIRECT_SINGLE = 2
 FCP_FLAG_PART_BF16 = 4
+FCP_FLAG_GRAD_BF16 = 8
 
 EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",

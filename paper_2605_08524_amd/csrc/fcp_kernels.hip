@@ -58,6 +58,24 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const unsigned char* lo, const uns
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
+// Stores one 32x32 accumulator tile as bf16 when a lane owns one output row: lane (l32, g) holds the
+// 16 values of columns 8*q4 + 4*g .. +3 (q4 = 0..3) of its row, its partner (lane ^ 32, same row)
+// the other four of every group of eight.  The two trade halves so that each stores 16 contiguous
+// bytes (8 columns): the lower lane keeps the even groups, the upper lane the odd ones.
+// dst = first of the tile's 32 columns in this lane's row.  Both lanes of a row must be active.
+__device__ __forceinline__ void store_tile_bf16(uint16_t* dst, const f32x16& x, float mul, int g) {
+#pragma unroll
+  for (int m = 0; m < 2; m++) {
+    const uint32_t e0 = pack_bf16(x[8 * m] * mul, x[8 * m + 1] * mul), e1 = pack_bf16(x[8 * m + 2] * mul, x[8 * m + 3] * mul);
+    const uint32_t f0 = pack_bf16(x[8 * m + 4] * mul, x[8 * m + 5] * mul), f1 = pack_bf16(x[8 * m + 6] * mul, x[8 * m + 7] * mul);
+    // swap(x, y): lanes 32-63 of x trade places with lanes 0-31 of y
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(e0, f0, false, false);
+    const u32x2 t = __builtin_amdgcn_permlane32_swap(e1, f1, false, false);
+    const u32x4 h = {r[0], t[0], r[1], t[1]};
+    *reinterpret_cast<u32x4*>(dst + 16 * m + 8 * g) = h;
+  }
+}
+
 // LDS accesses through 32-bit LDS addresses kept in registers: a tile buffer switch is then one
 // add per address (in place) and row / tile offsets fold into the instruction's immediate field.
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
@@ -524,22 +542,9 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
       const int64_t off = row * q_row_stride + (int64_t)head * D;
       if (to_final ? !a.o_is_f32 : a.part_is_bf16) {
-        // A lane holds columns 8 q4 + 4 g .. + 3 of its row, its partner (lane ^ 32, same row) the other four of
-        // every group of eight.  The two trade halves so that each stores 16 contiguous bytes (8 columns):
-        // the lower lane keeps the even groups, the upper lane the odd ones.
         uint16_t* op = reinterpret_cast<uint16_t*>(to_final ? a.o : a.o_part) + off;
 #pragma unroll
-        for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-          for (int m = 0; m < 2; m++) {
-            const uint32_t e0 = pack_bf16(o[dt][8 * m] * inv, o[dt][8 * m + 1] * inv), e1 = pack_bf16(o[dt][8 * m + 2] * inv, o[dt][8 * m + 3] * inv);
-            const uint32_t f0 = pack_bf16(o[dt][8 * m + 4] * inv, o[dt][8 * m + 5] * inv), f1 = pack_bf16(o[dt][8 * m + 6] * inv, o[dt][8 * m + 7] * inv);
-            // swap(x, y): lanes 32-63 of x trade places with lanes 0-31 of y
-            const u32x2 r = __builtin_amdgcn_permlane32_swap(e0, f0, false, false);
-            const u32x2 t = __builtin_amdgcn_permlane32_swap(e1, f1, false, false);
-            const u32x4 h = {r[0], t[0], r[1], t[1]};
-            *reinterpret_cast<u32x4*>(op + dt * 32 + 16 * m + 8 * g) = h;
-          }
+        for (int dt = 0; dt < DT; dt++) store_tile_bf16(op + dt * 32, o[dt], inv, g);
       } else {
         float* op = reinterpret_cast<float*>(to_final ? a.o : a.o_part) + off;
 #pragma unroll
@@ -748,7 +753,7 @@ struct BwdArgs {
   const float* lse2; const float* dls;     // head-major [Hq][T_q]: LSE*log2(e) (+inf for empty rows), D*scale
   // dq_kernel<D, true> computes those two itself from O, LSE and dO and writes them for dkdv_kernel
   const void* o; const float* lse; int32_t o_is_f32; float* lse2_out; float* dls_out;
-  float* dq; float* dk; float* dv;
+  void* dq; void* dk; void* dv;    // fp32, or bf16 in the GRAD_BF16 instances of the kernels
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
   int64_t t_q;
   int32_t n_q_heads, n_kv_heads;
@@ -787,7 +792,7 @@ struct StepIter {
 constexpr int kDkdvBufs = 7;        // ring of LDS step buffers
 constexpr int kNoMask = 1 << 30;    // diagonal threshold of a step that needs no mask
 
-template <int D>
+template <int D, bool GRAD_BF16>
 __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
@@ -979,13 +984,18 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       for (int n = 0; n < NN; n++) {
         const int kv_r = (n0 + n) * 32 + l32;
         if (kv_r < it.kv_rows) {
-          const int64_t off = (int64_t)(it.kv_start + kv_r) * kv_row_stride + (int64_t)it.kv_head * D + cdt * 32 + 4 * g;
+          const int64_t off = (int64_t)(it.kv_start + kv_r) * kv_row_stride + (int64_t)it.kv_head * D + cdt * 32;
+          if constexpr (GRAD_BF16) {
+            store_tile_bf16(reinterpret_cast<uint16_t*>(a.dk) + off, acc_k[n], 1.0f, g);
+            store_tile_bf16(reinterpret_cast<uint16_t*>(a.dv) + off, acc_v[n], 1.0f, g);
+          } else {
 #pragma unroll
-          for (int q4 = 0; q4 < 4; q4++) {
-            f32x4 wk = {acc_k[n][4 * q4], acc_k[n][4 * q4 + 1], acc_k[n][4 * q4 + 2], acc_k[n][4 * q4 + 3]};
-            f32x4 wv = {acc_v[n][4 * q4], acc_v[n][4 * q4 + 1], acc_v[n][4 * q4 + 2], acc_v[n][4 * q4 + 3]};
-            *reinterpret_cast<f32x4*>(a.dk + off + 8 * q4) = wk;
-            *reinterpret_cast<f32x4*>(a.dv + off + 8 * q4) = wv;
+            for (int q4 = 0; q4 < 4; q4++) {
+              f32x4 wk = {acc_k[n][4 * q4], acc_k[n][4 * q4 + 1], acc_k[n][4 * q4 + 2], acc_k[n][4 * q4 + 3]};
+              f32x4 wv = {acc_v[n][4 * q4], acc_v[n][4 * q4 + 1], acc_v[n][4 * q4 + 2], acc_v[n][4 * q4 + 3]};
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.dk) + off + 8 * q4 + 4 * g) = wk;
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.dv) + off + 8 * q4 + 4 * g) = wv;
+            }
           }
         }
       }
@@ -1122,7 +1132,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 // K rows past a ragged end are zero in LDS, so their dS contributes nothing: only the
 // diagonal needs a mask.  Every dQ row has one writer: plain stores, deterministic.
 // =====================================================================================
-template <int D, bool WITH_D>
+template <int D, bool WITH_D, bool GRAD_BF16>
 __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
@@ -1331,14 +1341,20 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
       switch_buffer();
     }
     if (row_ok) {
-      float* op = a.dq + (int64_t)(q_start + my_row) * q_row_stride + (int64_t)head * D;
+      const int64_t off = (int64_t)(q_start + my_row) * q_row_stride + (int64_t)head * D;
+      if constexpr (GRAD_BF16) {
 #pragma unroll
-      for (int dt = 0; dt < DT; dt++)
+        for (int dt = 0; dt < DT; dt++) store_tile_bf16(reinterpret_cast<uint16_t*>(a.dq) + off + dt * 32, acc[dt], 1.0f, g);
+      } else {
+        float* op = reinterpret_cast<float*>(a.dq) + off;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
-        }
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
+            *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
+          }
+      }
     }
     __syncthreads();
   }
@@ -1551,7 +1567,7 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
 }
 
 extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                       const void* d_o, float* dk, float* dv, void* workspace, void* stream) {
+                                       const void* d_o, void* dk, void* dv, void* workspace, void* stream) {
   WsLayout L;
   BwdArgs a;
   int rc = fill_bwd_args(p, &L, &a, workspace);
@@ -1561,14 +1577,16 @@ extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, cons
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dk = dk; a.dv = dv;
   int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(dkdv_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(dkdv_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  const bool gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0;
+  void (*kern)(BwdArgs) = p->head_dim == 128 ? (gb ? dkdv_kernel<128, true> : dkdv_kernel<128, false>)
+                                             : (gb ? dkdv_kernel<64, true> : dkdv_kernel<64, false>);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch("fcp_block_attn_bwd_dkdv");
 }
 
 // o / lse == NULL: the per-row scalars come from fcp_bwd_preprocess; else the kernel computes and publishes them.
 static int launch_dq(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,
-                     const void* o, const float* lse, const void* d_o, float* dq, void* workspace, void* stream) {
+                     const void* o, const float* lse, const void* d_o, void* dq, void* workspace, void* stream) {
   WsLayout L;
   BwdArgs a;
   int rc = fill_bwd_args(p, &L, &a, workspace);
@@ -1578,28 +1596,27 @@ static int launch_dq(const char* who, const fcp_problem* p, const void* q, const
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dq = dq;
   const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
-  const bool with_d = o != nullptr;
+  const bool with_d = o != nullptr, gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0, d128 = p->head_dim == 128;
   if (with_d) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     a.o = o; a.lse = lse; a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
     a.dls_out = reinterpret_cast<float*>(ws + L.off_dls);
     a.lse2_out = reinterpret_cast<float*>(ws + L.off_lse2);
-    if (p->head_dim == 128) hipLaunchKernelGGL((dq_kernel<128, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL((dq_kernel<64, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  } else {
-    if (p->head_dim == 128) hipLaunchKernelGGL((dq_kernel<128, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL((dq_kernel<64, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   }
+  void (*kern)(BwdArgs) =
+      with_d ? (d128 ? (gb ? dq_kernel<128, true, true> : dq_kernel<128, true, false>) : (gb ? dq_kernel<64, true, true> : dq_kernel<64, true, false>))
+             : (d128 ? (gb ? dq_kernel<128, false, true> : dq_kernel<128, false, false>) : (gb ? dq_kernel<64, false, true> : dq_kernel<64, false, false>));
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch(who);
 }
 
 extern "C" int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                     const void* d_o, float* dq, void* workspace, void* stream) {
+                                     const void* d_o, void* dq, void* workspace, void* stream) {
   return launch_dq("fcp_block_attn_bwd_dq", p, q, k, v, nullptr, nullptr, d_o, dq, workspace, stream);
 }
 
 extern "C" int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, const void* k, const void* v,
-                                       const void* o, const float* lse, const void* d_o, float* dq,
+                                       const void* o, const float* lse, const void* d_o, void* dq,
                                        void* workspace, void* stream) {
   if (!o || !lse) {
     int rc = validate_problem(p);
@@ -1612,7 +1629,7 @@ extern "C" int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, cons
 
 extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
                                   const void* o, const float* lse, const void* d_o,
-                                  float* dq, float* dk, float* dv, void* workspace, void* stream) {
+                                  void* dq, void* dk, void* dv, void* workspace, void* stream) {
   if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace) {
     int rc = validate_problem(p);
     if (rc) return rc;

@@ -49,9 +49,10 @@ class DevicePath:
         self.queue_build_ms = (time.perf_counter() - t0) * 1e3     # host: work items + one upload (returns when it is done)
         if backward:
             self.d_o = to_dev_bf16(wl.d_o(), device)
-            self.dq = torch.full((max(1, p.t_q), Hq, d), nan, **f32)
-            self.dk = torch.full((max(1, p.t_kv), Hkv, d), nan, **f32)
-            self.dv = torch.full((max(1, p.t_kv), Hkv, d), nan, **f32)
+            g_dtype = torch.bfloat16 if (flags & B.FCP_FLAG_GRAD_BF16) else torch.float32
+            self.dq = torch.full((max(1, p.t_q), Hq, d), nan, dtype=g_dtype, device=device)
+            self.dk = torch.full((max(1, p.t_kv), Hkv, d), nan, dtype=g_dtype, device=device)
+            self.dv = torch.full((max(1, p.t_kv), Hkv, d), nan, dtype=g_dtype, device=device)
 
     def fwd(self):
         if self.problem.flags & B.FCP_FLAG_DIRECT_SINGLE:
@@ -97,5 +98,6 @@ def run_path(wl, device, backward=False, flags=0, softmax_scale=0.0):
                lse_part=dp.lse_part[: p.n_slot_rows].cpu().numpy(),
                o=dp.o[: p.t_q].float().cpu().numpy(), lse=dp.lse[: p.t_q].cpu().numpy())
     if backward:
-        out.update(dq=dp.dq[: p.t_q].cpu().numpy(), dk=dp.dk[: p.t_kv].cpu().numpy(), dv=dp.dv[: p.t_kv].cpu().numpy())
+        out.update(dq=dp.dq[: p.t_q].float().cpu().numpy(), dk=dp.dk[: p.t_kv].float().cpu().numpy(),
+                   dv=dp.dv[: p.t_kv].float().cpu().numpy())
     return out

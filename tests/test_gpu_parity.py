@@ -301,6 +301,24 @@ def test_distributed_share_of_the_most_loaded_worker(n_workers):
     assert res["o"].shape[0] == int(w_m[heavy])
 
 
+@pytest.mark.parametrize("cfg,seed", [(1, 0), (1, 1)])
+def test_bf16_gradients_are_the_fp32_gradients_rounded_once(cfg, seed):
+    """FCP_FLAG_GRAD_BF16: the kernels round their fp32 sums to bf16 (nearest-even) as they store them.  The fp32 path
+    is bit-reproducible, so the bf16 result must equal the fp32 result rounded, bit for bit; and it still meets the
+    bars against the oracle once the oracle's own values are allowed half a bf16 ulp."""
+    GRAD_BF16 = 8
+    wl = workloads.make_workload(cfg, seed)
+    dev = torch.device("cuda:0")
+    _say(f"bf16 gradients cfg {cfg} seed {seed}")
+    a = run_path(wl, dev, backward=True, flags=F32)
+    b = run_path(wl, dev, backward=True, flags=F32 | GRAD_BF16)
+    ref = dict(zip(("dq", "dk", "dv"), orc.worker_bwd(wl.q(), wl.k(), wl.v(), wl.d_o(), wl.seq_lens, wl.block_size, wl.causal)))
+    for name in ("dq", "dk", "dv"):
+        want = torch.from_numpy(a[name]).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(want, b[name]), name
+        _check(name, b[name], ref[name], tol_abs=TOL_ABS + float(np.abs(ref[name]).max()) * 2.0 ** -9)
+
+
 def test_mfma_probe_runs_and_random_operands_are_not_faster_than_zeros():
     """The measurement aid behind the benchmark's sustained-MFMA figures: it must run, leave finite
     checksums (zeros for zero operands), and the chip must not hold a higher rate on random operands."""
