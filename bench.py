@@ -27,9 +27,9 @@ PEAK_HBM_GBS = 8000.0
 # plain copy of known size in the same runs (profiles/cfg5_training_step_hbm_traffic.txt); None
 # for a workload or kernel that has not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.772e9,
-    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.467e9,
-    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 4.394e9,
+    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.781e9,
+    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.255e9,
+    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 4.430e9,
 }
 
 
