@@ -751,7 +751,7 @@ __global__ void __launch_bounds__(256) delta_kernel(const void* o, int o_is_f32,
 struct BwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse2; const float* dls;     // head-major [Hq][T_q]: LSE*log2(e) (+inf for empty rows), D*scale
-  // dq_kernel<D, true> computes those two itself from O, LSE and dO and writes them for dkdv_kernel
+  // dq_kernel<D, true, *> computes those two itself from O, LSE and dO and writes them for dkdv_kernel
   const void* o; const float* lse; int32_t o_is_f32; float* lse2_out; float* dls_out;
   void* dq; void* dk; void* dv;    // fp32, or bf16 in the GRAD_BF16 instances of the kernels
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
