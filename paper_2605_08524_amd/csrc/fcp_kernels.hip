@@ -225,9 +225,9 @@ __device__ __forceinline__ void retire(int32_t* counter, int32_t* done) {
 // places the exponentials of tile i, and later the maximum of tile i+1, between them, so the
 // matrix pipe does not wait for the vector ALU inside a wave.  [K | V] tiles sit in a ring of
 // four LDS buffers filled by LDS-DMA three tiles ahead (all 8 waves share one stream); one
-// workgroup barrier per tile.  Iterations before the first and past the last tile of an item
-// run on fully masked scores (P = 0), so every iteration is the same instruction stream, and
-// the ring runs on from item to item.
+// workgroup barrier per tile.  The first iteration of an item computes S of its first tile only
+// and the last one only adds the last tile to O, so the pipeline fill costs no MFMAs; all
+// iterations issue the same tile loads, and the ring runs on from item to item.
 // =====================================================================================
 constexpr int kFwdTileN = 64;   // KV rows per LDS tile
 constexpr int kFwdBufs = 4;     // ring of [K | V] tile buffers
@@ -413,14 +413,18 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
 
     // One iteration.  sc = scores of tile i (masked, maximum already folded into m_run);
     // sn receives S^T of tile i+1.
-    auto iteration = [&](f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+    // FIRST: nothing to exponentiate or to add to O yet (S^T of tile 0 only); LAST: no next tile (O += V P of the
+    // last tile only).  An item thus costs one iteration's worth of MFMAs per tile and nothing for the pipeline fill.
+    auto iteration = [&](auto first_t, auto last_t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+      constexpr bool FIRST = decltype(first_t)::value, LAST = decltype(last_t)::value;
       const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
       u32x4 pb[4];                    // P^T of tile i as four B operands (rt, j)
       float rs = 0.f;
       float p_prev = 0.f;
       // the exponential of the NEXT element is issued before this one is consumed, so its latency
       // does not sit in a dependent chain (the wave issues in order)
-      float p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][0], a.scale_log2, -m_use));
+      float p_ahead = 0.f;
+      if constexpr (!FIRST) p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][0], a.scale_log2, -m_use));
       auto expo = [&](int e) {        // element e = (rt, r) of tile i
         const int r = e & 15;
         const float p = p_ahead;
@@ -433,7 +437,11 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         } else p_prev = p;
       };
       // ---- phase 1: S^T(i+1) = K Q^T (two 32-row halves); exponentials of tile i between the MFMAs
-      {
+      if constexpr (LAST) {
+        issue();
+#pragma unroll
+        for (int e = 0; e < 24; e++) expo(e);
+      } else {
         u32x4 op[PF];
 #pragma unroll
         for (int u = 0; u < PF; u++) op[u] = lds_read16(kk_off[u / 2] + (u & 1) * 32 * (D * 2));
@@ -447,14 +455,16 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
           sn[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[u % PF]), qf[kc], sn[rt], 0, 0, 0);
           if (u + PF < NS1) op[u % PF] = lds_read16(kk_off[(u + PF) / 2] + ((u + PF) & 1) * 32 * (D * 2));
           // 24 of the 32 elements in this phase
+          if constexpr (!FIRST) {
 #pragma unroll
-          for (int e = u * 24 / NS1; e < (u + 1) * 24 / NS1; e++) expo(e);
+            for (int e = u * 24 / NS1; e < (u + 1) * 24 / NS1; e++) expo(e);
+          }
           if (u == NS1 / 2) issue();
           __builtin_amdgcn_sched_barrier(0);
         }
       }
       // ---- phase 2: O^T += V^T P^T; the rest of the exponentials
-      {
+      if constexpr (!FIRST) {
         u32x4 op[PF];
         auto fetch = [&](int u) {
           const uint32_t rows = 16 * (u / DT) * (D * 2);
@@ -477,7 +487,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
       __syncthreads();
       // ---- mask of tile i+1 (only tiles that touch the diagonal or a ragged end, or lie past the
       // end of the item), then its maximum
-      {
+      if constexpr (!LAST) {
         const TileMeta tm = meta[0];
         // readfirstlane: the condition is wave-uniform, but the compiler does not know it and would
         // otherwise run the rare path on every tile as 64 compares and selects
@@ -493,24 +503,26 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
               if (rt * 32 + 8 * (r >> 2) + (r & 3) > limit) sn[rt][r] = -INFINITY;
         }
       }
-      float mx = fmaxf(sn[0][0], sn[1][0]);
+      if constexpr (!LAST) {
+        float mx = fmaxf(sn[0][0], sn[1][0]);
 #pragma unroll
-      for (int r = 1; r < 16; r++) mx = fmaxf(fmaxf(mx, sn[0][r]), sn[1][r]);
-      // ---- online softmax bookkeeping for tile i+1, in the log2 domain.  The reference maximum
-      // m_run only moves when some row's maximum exceeds it by more than kRescaleSlack (a
-      // wave-uniform decision): any reference gives the same O and LSE as long as exp2 stays in
-      // range, and P <= 2^slack is harmless in bf16/fp32.  Most tiles skip the rescaling of O.
-      mx = fmaxf(mx, xor32(mx)) * a.scale_log2;
-      if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // m_run = -inf -> 0
-        m_run = m_new;
-        l_run *= alpha;
+        for (int r = 1; r < 16; r++) mx = fmaxf(fmaxf(mx, sn[0][r]), sn[1][r]);
+        // ---- online softmax bookkeeping for tile i+1, in the log2 domain.  The reference maximum
+        // m_run only moves when some row's maximum exceeds it by more than kRescaleSlack (a
+        // wave-uniform decision): any reference gives the same O and LSE as long as exp2 stays in
+        // range, and P <= 2^slack is harmless in bf16/fp32.  Most tiles skip the rescaling of O.
+        mx = fmaxf(mx, xor32(mx)) * a.scale_log2;
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+          const float m_new = fmaxf(m_run, mx);
+          const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // m_run = -inf -> 0
+          m_run = m_new;
+          l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < DT; dt++)
+          for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+            for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+        }
       }
       // ---- rotate the ring
       meta[0] = meta[1]; meta[1] = meta[2];
@@ -526,11 +538,23 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         b_v = (b_v == NB - 1) ? 0 : b_v + 1;
       }
     };
-    for (int i = 0; i + 1 < n_it; i += 2) {
-      iteration(s_a, s_b);
-      iteration(s_b, s_a);
+    const std::true_type yes;
+    const std::false_type no;
+    iteration(yes, no, s_a, s_b);          // S^T of tile 0 (of nothing, masked, for an item without tiles)
+    if (n_it >= 2) {
+      int rem = n_it - 2;                  // iterations that do both phases; they alternate (s_b, s_a), (s_a, s_b)
+      for (; rem >= 2; rem -= 2) {
+        iteration(no, no, s_b, s_a);
+        iteration(no, no, s_a, s_b);
+      }
+      if (rem) {
+        iteration(no, no, s_b, s_a);       // a tail, not a branch inside the loop (which costs dozens of spills)
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < 2; rt++) s_a[rt] = s_b[rt];
+      }
+      iteration(no, yes, s_a, s_b);        // O += V P of the last tile
     }
-    if (n_it & 1) iteration(s_a, s_b);     // a tail, not a branch inside the loop (which costs dozens of spills)
     dma_wait();         // the look-ahead loads past the end of the item (zero tiles)
 
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
