@@ -301,6 +301,21 @@ def test_distributed_share_of_the_most_loaded_worker(n_workers):
     assert res["o"].shape[0] == int(w_m[heavy])
 
 
+@pytest.mark.parametrize("case", [3, 5, 6, 8, 11, 12])
+def test_bf16_gradients_edge_cases(case):
+    """FCP_FLAG_GRAD_BF16 on ragged, non-causal, shared and grouped-head cases of both head sizes: bit-equal to the
+    fp32 gradients rounded once; rows the worker does not own stay untouched in both."""
+    lens, bs, causal, c, hq, hkv, d, owned = EDGE[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=100 + case, name=f"edge{case}")
+    dev = torch.device("cuda:0")
+    _say(f"bf16 gradients {wl.name}")
+    a = run_path(wl, dev, backward=True, flags=F32)
+    b = run_path(wl, dev, backward=True, flags=F32 | 8)
+    for name in ("dq", "dk", "dv"):
+        want = torch.from_numpy(a[name]).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(want, b[name], equal_nan=True), name
+
+
 @pytest.mark.parametrize("cfg,seed", [(1, 0), (1, 1)])
 def test_bf16_gradients_are_the_fp32_gradients_rounded_once(cfg, seed):
     """FCP_FLAG_GRAD_BF16: the kernels round their fp32 sums to bf16 (nearest-even) as they store them.  The fp32 path
