@@ -284,6 +284,32 @@ def test_whole_step_replays_from_a_hip_graph():
             torch.cuda.synchronize(dev)
 
 
+def test_side_stream_gives_the_default_streams_bits():
+    """Every launch goes to the stream the caller names and nothing else orders the work: a step enqueued on a side
+    stream (default priority), after an event that the inputs' stream recorded, equals the default-stream step bit for bit."""
+    from paper_2605_08524_amd.harness import DevicePath
+    wl = workloads.custom_workload([900, 50, 1300], 128, 1, 4, 4, 2, 128, seed=31, name="side-stream")
+    dev = torch.device("cuda:0")
+    _say(f"case {wl.name}")
+    dp = DevicePath(wl, dev, flags=F32, backward=True)
+    outs = ("o", "lse", "dq", "dk", "dv")
+    dp.fwd(); dp.merge(); dp.bwd()
+    torch.cuda.synchronize(dev)
+    want = [getattr(dp, n).clone() for n in outs]
+    for n in outs:
+        getattr(dp, n).fill_(float("nan"))
+    ready = torch.cuda.Event()
+    ready.record(torch.cuda.current_stream(dev))
+    side = torch.cuda.Stream(device=dev)
+    side.wait_event(ready)
+    dp.stream = side
+    dp.fwd(); dp.merge(); dp.bwd()
+    side.synchronize()
+    dp.stream = None
+    for n, w in zip(outs, want):
+        assert torch.equal(getattr(dp, n).view(torch.int32), w.view(torch.int32)), n
+
+
 @pytest.mark.parametrize("n_workers", [4])
 def test_distributed_share_of_the_most_loaded_worker(n_workers):
     """Block distributor -> planner -> kernels: the share that the greedy assignment gives the most loaded of
