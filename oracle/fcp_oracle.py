@@ -381,11 +381,6 @@ def merge_partials(o_part, lse_part, plan):
     return o, lse
 
 
-def bwd_delta(o, d_o):
-    """D[t, h] = sum_c dO[t,h,c] O[t,h,c] (fp64)."""
-    return np.sum(np.asarray(o, dtype=np.float64) * np.asarray(d_o, dtype=np.float64), axis=-1)
-
-
 # --------------------------------------------------------------------------
 # FLOP model used for the reported throughput
 # --------------------------------------------------------------------------

@@ -108,26 +108,31 @@ def pack_units(blocks, m, c, block_size):
 # Greedy Load-Balanced Assignment
 # --------------------------------------------------------------------------
 def assign_blocks(m, c, n_workers, alpha=1.0, beta=1.0, mem_limit=0, delta=0.0):
-    """The appendix algorithm, step by step.  Returns (owner [K], worker_m [N], worker_c [N])."""
+    """Greedy assignment of blocks to workers (appendix "Block Assignment Algorithm").
+
+    Every worker should end up with the batch's mean memory and mean compute; a block's size is the
+    larger of its memory and compute cost relative to those means; blocks are placed largest first,
+    each on the worker that would be least loaded afterwards (load = the larger of its weighted
+    relative memory and compute), among the workers whose memory stays within mem_limit * (1 + delta).
+    Returns (owner [K], worker_m [N], worker_c [N])."""
     K, N = len(m), int(n_workers)
     if N <= 0:
         raise ValueError("no workers")
     m = [int(x) for x in m]
     c = [int(x) for x in c]
-    # step 1: desired loads per worker (sums are exact integers)
+    # mean cost per worker (the sums are exact integers)
     m_hat = float(sum(m)) / N
     c_hat = float(sum(c)) / N
     # a cost that is zero for every block drops out of both the key and the load
     def rel(x, x_hat):
         return float(x) / x_hat if x_hat > 0.0 else 0.0
-    # step 2: descending by max(m_i / m_hat, c_i / c_hat), stable
+    # largest relative cost first; equal keys keep their block order
     key = [max(rel(m[i], m_hat), rel(c[i], c_hat)) for i in range(K)]
     order = sorted(range(K), key=lambda i: -key[i])
-    # step 3
     w_m, w_c = [0] * N, [0] * N
     owner = [-1] * K
     cap = float(mem_limit) * (1.0 + float(delta))
-    # steps 4-7
+    # ties between workers go to the lowest index
     for i in order:
         best, best_load = -1, 0.0
         for w in range(N):

@@ -323,3 +323,44 @@ def test_flop_model():
     plan = orc.plan_blocks([8], 4, 1, 0)
     f, b = orc.flops(plan, 3, 16)
     assert f == 4 * 16 * 3 * 36 and b == 10 * 16 * 3 * 36
+
+
+def test_bf16_decoding_matches_the_format():
+    """bf16 = the upper 16 bits of an IEEE binary32: sign, 8 exponent bits (bias 127), 7 fraction
+    bits.  Values the format itself fixes, then every one of the 65536 bit patterns against
+    PyTorch's own bfloat16 decoding (independent code)."""
+    fixed = {0x0000: 0.0, 0x3F80: 1.0, 0xBF80: -1.0, 0xC000: -2.0, 0x3FC0: 1.5, 0x4049: 3.140625, 0x3DCD: 0.10009765625,
+             0x0001: 2.0 ** -133, 0x0080: 2.0 ** -126, 0x7F7F: (2.0 - 2.0 ** -7) * 2.0 ** 127,
+             0x7F80: math.inf, 0xFF80: -math.inf}
+    for bits, want in fixed.items():
+        got = orc.bf16_to_f64(np.asarray([bits], dtype=np.uint16))
+        assert got.dtype == np.float64 and got.shape == (1,)
+        assert got[0] == want, (hex(bits), got[0], want)
+    assert math.copysign(1.0, orc.bf16_to_f64(np.asarray([0x8000], dtype=np.uint16))[0]) == -1.0     # -0.0
+    assert np.isnan(orc.bf16_to_f64(np.asarray([0x7FC0], dtype=np.uint16))[0])
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):      # signalling NaN patterns are among them
+        got = orc.bf16_to_f64(every.reshape(256, 256))
+    want = torch.from_numpy(every.view(np.int16).copy()).view(torch.bfloat16).double().numpy().reshape(256, 256)
+    assert got.shape == (256, 256)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan]) and np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # the direct formula, element by element, on a sample of normal and subnormal patterns
+    for bits in (0x0001, 0x007F, 0x0080, 0x1234, 0x3F81, 0x4A5B, 0x7F7F, 0x8001, 0xBEEF, 0xFF7F):
+        sign, e, f = bits >> 15, (bits >> 7) & 0xFF, bits & 0x7F
+        val = (f / 128.0) * 2.0 ** -126 if e == 0 else (1.0 + f / 128.0) * 2.0 ** (e - 127)
+        assert orc.bf16_to_f64(np.asarray([bits], dtype=np.uint16))[0] == (-val if sign else val)
+
+
+def test_input_generators_do_not_need_the_library():
+    """The seeded generators serve the oracle and the library alike; importing them must not load
+    the product's shared library (the oracle's pins run where it has not been built)."""
+    import subprocess
+    import sys
+    code = ("import sys; from paper_2605_08524_amd import workloads; "
+            "assert 'paper_2605_08524_amd.binding' not in sys.modules; "
+            "import oracle.fcp_oracle; assert 'paper_2605_08524_amd.binding' not in sys.modules; print('ok')")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True)
+    assert res.returncode == 0 and res.stdout.strip() == "ok", res.stderr
