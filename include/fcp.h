@@ -161,6 +161,25 @@ int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, c
                            void* workspace, void* stream);
 
 /*
+ * fcp_block_attn_fwd_static -- fcp_block_attn_fwd for callers that cannot allocate device memory or keep a
+ * workspace (code under HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc).
+ *
+ * Same result as fcp_queue_build + fcp_block_attn_fwd, bit for bit, with no workspace argument: the
+ * forward's queue tables (header with the queue counters, resolved pairs, forward work items) are built
+ * on the host at every call and copied into a fixed array of 2 MiB inside the library's device image,
+ * which every device the library runs on holds until the process ends.  The call allocates no device
+ * memory (no hipMalloc / hipFree, no allocating library routine); it waits on `stream` for its table
+ * copy, then enqueues the kernel and returns.
+ * Limits and errors: FCP_ERR_BUFFER_TOO_SMALL if the tables need more than 2 MiB (about 30 000 forward
+ * work items: the packed 64K-token training batch fits, the 1M-token share does not);
+ * FCP_ERR_INVALID_ARG with FCP_FLAG_DIRECT_SINGLE (every slot goes to the partial buffers here);
+ * otherwise as fcp_block_attn_fwd.  All calls on one device share that device's array, counters
+ * included: calls that overlap in time on one device race, whatever their streams.
+ */
+int fcp_block_attn_fwd_static(const fcp_problem* p, const void* q, const void* k, const void* v,
+                              void* o_part, float* lse_part, void* stream);
+
+/*
  * fcp_merge_partials -- reduce the partials of each query block to the final output.
  *
  * Paper: section "Context Parallelism" (intermediate results over slices are reduced to the

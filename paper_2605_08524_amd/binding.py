@@ -31,7 +31,7 @@ FCP_FLAG_GRAD_BF16 = 8
 EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
-    "fcp_block_attn_bwd_dq_d",
+    "fcp_block_attn_bwd_dq_d", "fcp_block_attn_fwd_static",
     "fcp_last_error", "fcp_device_info", "fcp_mfma_probe",
     "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
     "fcp_coalesce_stages", "fcp_pack_units",
@@ -74,6 +74,7 @@ def _load():
     lib.fcp_queue_build.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     lib.fcp_block_attn_fwd_out.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 9
+    lib.fcp_block_attn_fwd_static.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_merge_partials.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 6
     lib.fcp_block_attn_bwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 11
     lib.fcp_bwd_preprocess.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 5
@@ -193,6 +194,11 @@ def fcp_block_attn_fwd(problem: Problem, q, k, v, o_part, lse_part, workspace, s
 def fcp_block_attn_fwd_out(problem: Problem, q, k, v, o_part, lse_part, o, lse, workspace, stream=None):
     _check(_lib.fcp_block_attn_fwd_out(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o_part), _ptr(lse_part),
                                        _ptr(o), _ptr(lse), _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_fwd_static(problem: Problem, q, k, v, o_part, lse_part, stream=None):
+    _check(_lib.fcp_block_attn_fwd_static(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o_part), _ptr(lse_part),
+                                          _stream(stream)))
 
 
 def fcp_merge_partials(problem: Problem, o_part, lse_part, o, lse, workspace, stream=None):

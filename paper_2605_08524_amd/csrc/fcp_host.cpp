@@ -305,21 +305,14 @@ extern "C" int fcp_workspace_bytes(const fcp_problem* p, size_t* bytes) {
   return FCP_OK;
 }
 
-extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = validate_problem(p);
-  if (rc) return rc;
-  WsLayout L;
-  rc = compute_layout(p, &L);
-  if (rc) return rc;
-  if (!workspace || ((uintptr_t)workspace & 255)) {
-    set_error("fcp_queue_build: workspace is NULL or not 256-byte aligned"); return FCP_ERR_INVALID_ARG;
-  }
-  if (workspace_bytes < L.total) {
-    set_error("fcp_queue_build: workspace too small (%zu < %zu)", workspace_bytes, L.total);
-    return FCP_ERR_BUFFER_TOO_SMALL;
-  }
-  const size_t upload = L.off_dls;   // everything before the backward scratch region
-  std::vector<unsigned char> host(upload, 0);
+// The host image of the workspace sections that the kernels read: header (zeroed counters, queue
+// ranges, zero / +inf pages), resolved pairs, forward items and, unless forward_only, the backward,
+// dQ and merge tables.  `host` is resized to the image (everything before the backward scratch
+// region, or before the backward dependency lists when forward_only).
+int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward_only, std::vector<unsigned char>* image) {
+  const size_t upload = forward_only ? L.off_bwd_deps : L.off_dls;
+  image->assign(upload, 0);
+  std::vector<unsigned char>& host = *image;
   WsHeader* hdr = reinterpret_cast<WsHeader*>(host.data());
   for (float& x : hdr->infs) x = INFINITY;
   DevPair* dpairs = reinterpret_cast<DevPair*>(host.data() + L.off_pairs);
@@ -389,6 +382,7 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     if ((int64_t)flat.size() != L.n_fwd_items) { set_error("internal: forward item count mismatch"); return FCP_ERR_INVALID_ARG; }
     if (!flat.empty()) std::memcpy(host.data() + L.off_fwd_items, flat.data(), flat.size() * sizeof(QItem));
   }
+  if (forward_only) return FCP_OK;
   // ---- backward: dependency lists per KV block, one group per (KV block, KV head).
   {
     std::vector<int32_t> dep_count(p->n_kv_blocks + 1, 0);
@@ -526,7 +520,26 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
     }
     if (n != L.n_merge_items) { set_error("internal: merge item count mismatch"); return FCP_ERR_INVALID_ARG; }
   }
-  hipError_t e = hipMemcpyAsync(workspace, host.data(), upload, hipMemcpyHostToDevice, (hipStream_t)stream);
+  return FCP_OK;
+}
+
+extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_problem(p);
+  if (rc) return rc;
+  WsLayout L;
+  rc = compute_layout(p, &L);
+  if (rc) return rc;
+  if (!workspace || ((uintptr_t)workspace & 255)) {
+    set_error("fcp_queue_build: workspace is NULL or not 256-byte aligned"); return FCP_ERR_INVALID_ARG;
+  }
+  if (workspace_bytes < L.total) {
+    set_error("fcp_queue_build: workspace too small (%zu < %zu)", workspace_bytes, L.total);
+    return FCP_ERR_BUFFER_TOO_SMALL;
+  }
+  std::vector<unsigned char> host;
+  rc = build_queue_image(p, L, false, &host);
+  if (rc) return rc;
+  hipError_t e = hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
   if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) { set_error("fcp_queue_build: %s", hipGetErrorString(e)); return FCP_ERR_HIP; }
   return FCP_OK;

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "fcp.h"
 
 namespace fcp {
@@ -53,6 +55,7 @@ struct WsLayout {
 int validate_problem(const fcp_problem* p);           // host; sets the error text
 int compute_layout(const fcp_problem* p, WsLayout* L); // host
 void set_error(const char* fmt, ...);
+int build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward_only, std::vector<unsigned char>* image);  // host
 
 }  // namespace fcp
 #endif

@@ -19,6 +19,7 @@
 #include <cmath>
 #include <cstdint>
 #include <type_traits>
+#include <vector>
 
 #include "fcp_internal.h"
 
@@ -1519,6 +1520,65 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
 extern "C" int fcp_block_attn_fwd(const fcp_problem* p, const void* q, const void* k, const void* v,
                                   void* o_part, float* lse_part, void* workspace, void* stream) {
   return launch_fwd("fcp_block_attn_fwd", p, q, k, v, o_part, lse_part, nullptr, nullptr, workspace, stream);
+}
+
+// ---- forward without any allocation: the queue tables live in a fixed device array ----
+namespace fcp {
+constexpr size_t kStaticScratchBytes = 2u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// Device address of `scratch` on each device (the array's name is a host-side stand-in, not an
+// address a kernel can use; every device holds its own copy at its own address).
+static void* g_scratch_ptr[64] = {nullptr};
+
+static int static_scratch(void** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_error("fcp_block_attn_fwd_static: hipGetDevice: %s", hipGetErrorString(e)); return FCP_ERR_HIP; }
+  if (dev < 0 || dev >= 64) { set_error("fcp_block_attn_fwd_static: device index %d out of range", dev); return FCP_ERR_UNSUPPORTED; }
+  if (!g_scratch_ptr[dev]) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !sym) {
+      set_error("fcp_block_attn_fwd_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+      return FCP_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = sym;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return FCP_OK;
+}
+}  // namespace fcp
+
+extern "C" int fcp_block_attn_fwd_static(const fcp_problem* p, const void* q, const void* k, const void* v,
+                                         void* o_part, float* lse_part, void* stream) {
+  int rc = validate_problem(p);
+  if (rc) return rc;
+  if (p->flags & FCP_FLAG_DIRECT_SINGLE) {
+    set_error("fcp_block_attn_fwd_static: FCP_FLAG_DIRECT_SINGLE is not supported here (all slots go to the partial buffers)");
+    return FCP_ERR_INVALID_ARG;
+  }
+  WsLayout L;
+  rc = compute_layout(p, &L);
+  if (rc) return rc;
+  if (L.off_bwd_deps > kStaticScratchBytes) {
+    set_error("fcp_block_attn_fwd_static: the forward's queue tables need %zu bytes, the fixed scratch array holds %zu "
+              "(use fcp_queue_build + fcp_block_attn_fwd with a workspace of your own)", L.off_bwd_deps, kStaticScratchBytes);
+    return FCP_ERR_BUFFER_TOO_SMALL;
+  }
+  if (L.n_fwd_items == 0) return FCP_OK;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // The tables are rebuilt on every call (the array keeps the previous call's contents): header with
+  // zeroed counters, resolved pairs, forward items.  Host memory only; one copy; the copy is waited for
+  // because its source dies with this frame.
+  std::vector<unsigned char> image;
+  rc = build_queue_image(p, L, true, &image);
+  if (rc) return rc;
+  hipError_t e = hipMemcpyAsync(ws, image.data(), image.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) { set_error("fcp_block_attn_fwd_static: %s", hipGetErrorString(e)); return FCP_ERR_HIP; }
+  return launch_fwd("fcp_block_attn_fwd_static", p, q, k, v, o_part, lse_part, nullptr, nullptr, ws, stream);
 }
 
 extern "C" int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, const void* v,
