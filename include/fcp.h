@@ -244,22 +244,6 @@ const char* fcp_last_error(void);
 /* Persistent grid sizes used by the kernels on the current device (for reports). */
 int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int32_t* bwd_grid);
 
-/*
- * fcp_mfma_probe -- measurement aid, not part of the method: what the matrix pipes of this chip
- * sustain on the attention kernels' MFMA (v_mfma_f32_32x32x16_bf16) for given operand VALUES.
- *
- * Launches one kernel on `stream`: one workgroup of 8 waves per compute unit (two waves per SIMD,
- * as in the attention kernels), each wave issuing iters x 16 back-to-back MFMAs on operands held in
- * registers -- no LDS, no memory traffic, no other vector work.  The caller times the launch;
- * FLOPs = n_compute_units x 8 x iters x 16 x 32768.  The rate depends on the operand values because
- * the chip lowers its clock to stay inside its power limit: zeros or constants run near the published
- * peak, random values well below it.
- * operand_kind: 0 = zeros, 1 = every element 0.5, 2 = pseudo-random, approximately N(0,1).
- * out: device, at least 8 x n_compute_units floats (one checksum per wave; contents meaningless).
- * Errors: FCP_ERR_INVALID_ARG (NULL out, iters <= 0, unknown kind), FCP_ERR_HIP.
- */
-int fcp_mfma_probe(int32_t operand_kind, int32_t iters, float* out, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

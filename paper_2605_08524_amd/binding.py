@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfcp.so")
+# FCP_LIB_PATH (debugging only): another build of the same library, e.g. the one with host-side sanitizers
+LIB_PATH = os.environ.get("FCP_LIB_PATH") or os.path.join(_HERE, "libfcp.so")
 
 FCP_OK = 0
 FCP_ERR_INVALID_ARG = -1

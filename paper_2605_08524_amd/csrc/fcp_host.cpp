@@ -7,7 +7,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
+#include <utility>
 #include <vector>
 
 #include "fcp_internal.h"
@@ -155,6 +157,49 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   L->off_lse2 = off;        off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
   L->total = off;
   return FCP_OK;
+}
+
+// Layouts validated by fcp_queue_build, keyed by the workspace they were built into.  A launch on that
+// workspace with the same descriptor scalars reuses the layout instead of walking every table again: the
+// kernels read the device copy of the tables that fcp_queue_build made, so the host tables matter to a
+// launch only through their counts.  A workspace the registry does not know (or a descriptor that differs)
+// takes the full validation path.
+namespace {
+struct LayoutKey {
+  const void* workspace;
+  int32_t v[11];
+  bool operator==(const LayoutKey& o) const { return workspace == o.workspace && std::memcmp(v, o.v, sizeof(v)) == 0; }
+};
+LayoutKey make_key(const fcp_problem* p, const void* ws) {
+  return LayoutKey{ws, {p->n_q_heads, p->n_kv_heads, p->head_dim, p->block_size, p->flags & FCP_FLAG_DIRECT_SINGLE,
+                        p->n_kv_blocks, p->n_q_blocks, p->n_pairs, p->n_slots, p->n_slot_rows, 0}};
+}
+constexpr int kLayoutCacheSize = 32;
+std::mutex g_layout_mutex;
+std::pair<LayoutKey, WsLayout> g_layout_cache[kLayoutCacheSize];
+int g_layout_count = 0, g_layout_next = 0;
+}  // namespace
+
+void remember_layout(const fcp_problem* p, const void* workspace, const WsLayout& L) {
+  const LayoutKey key = make_key(p, workspace);
+  std::lock_guard<std::mutex> lock(g_layout_mutex);
+  for (int i = 0; i < g_layout_count; i++)
+    if (g_layout_cache[i].first.workspace == workspace) { g_layout_cache[i] = {key, L}; return; }
+  g_layout_cache[g_layout_next] = {key, L};
+  g_layout_next = (g_layout_next + 1) % kLayoutCacheSize;
+  g_layout_count = std::min(g_layout_count + 1, kLayoutCacheSize);
+}
+
+int layout_for(const fcp_problem* p, const void* workspace, WsLayout* L) {
+  if (p && workspace && p->softmax_scale >= 0.0f) {
+    const LayoutKey key = make_key(p, workspace);
+    std::lock_guard<std::mutex> lock(g_layout_mutex);
+    for (int i = 0; i < g_layout_count; i++)
+      if (g_layout_cache[i].first == key) { *L = g_layout_cache[i].second; return FCP_OK; }
+  }
+  int rc = validate_problem(p);
+  if (rc) return rc;
+  return compute_layout(p, L);
 }
 
 namespace {
@@ -542,5 +587,6 @@ extern "C" int fcp_queue_build(const fcp_problem* p, void* workspace, size_t wor
   hipError_t e = hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
   if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) { set_error("fcp_queue_build: %s", hipGetErrorString(e)); return FCP_ERR_HIP; }
+  remember_layout(p, workspace, L);
   return FCP_OK;
 }

@@ -54,6 +54,9 @@ struct WsLayout {
 
 int validate_problem(const fcp_problem* p);           // host; sets the error text
 int compute_layout(const fcp_problem* p, WsLayout* L); // host
+// the layout of a problem on a workspace: from the registry that fcp_queue_build fills, else validated and computed
+int layout_for(const fcp_problem* p, const void* workspace, WsLayout* L);   // host
+void remember_layout(const fcp_problem* p, const void* workspace, const WsLayout& L);
 void set_error(const char* fmt, ...);
 int build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward_only, std::vector<unsigned char>* image);  // host
 

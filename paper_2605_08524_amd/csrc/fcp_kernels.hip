@@ -22,6 +22,7 @@
 #include <vector>
 
 #include "fcp_internal.h"
+#include "fcp_probe.h"
 
 namespace fcp {
 
@@ -1154,8 +1155,8 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 //   S^T = K Q^T, dP^T = V dO^T       (A = K / V rows from LDS, B = Q / dO fragments in registers)
 //   P^T = exp2(S^T*c - LSE*log2e), dS^T = P^T o (dP^T - D) * scale     (LSE, D per lane)
 //   dQ^T += K^T dS^T                 (A = K by transpose reads, B = accumulator registers)
-// K rows past a ragged end are zero in LDS, so their dS contributes nothing: only the
-// diagonal needs a mask.  Every dQ row has one writer: plain stores, deterministic.
+// Columns past the diagonal or past a ragged end get P = 0.  Every dQ row has one writer: plain
+// stores, deterministic.
 // =====================================================================================
 template <int D, bool WITH_D, bool GRAD_BF16>
 __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
@@ -1310,8 +1311,11 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
 
       const bool diag = tp.kind == FCP_KIND_DIAG;
       if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
-        const bool need_mask = diag && tc0 + kFwdTileN - 1 > wave_row_lo;
-        const int limit = tile_off_q + my_row;      // last visible column of a DIAG pair
+        // wave-uniform: tiles that straddle the diagonal, and tiles that hold a ragged end (their K rows past
+        // the end are zero in LDS, but S = 0 there still gives P = exp2(-LSE), which overflows for a row whose
+        // logits are all strongly negative; inf * 0 would then poison the whole dQ row)
+        const bool need_mask = (diag && tc0 + kFwdTileN - 1 > wave_row_lo) || tc0 + kFwdTileN > tp.kv_len;
+        const int limit = diag ? tile_off_q + my_row : tp.kv_len - 1;      // last visible column for this lane
         // the two 32-row halves of the KV tile one after the other: half the live accumulators
 #pragma unroll
         for (int rt = 0; rt < 2; rt++) {
@@ -1488,10 +1492,8 @@ extern "C" int fcp_mfma_probe(int32_t operand_kind, int32_t iters, float* out, v
 
 static int launch_fwd(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,
                       void* o_part, float* lse_part, void* o, float* lse, void* workspace, void* stream) {
-  int rc = validate_problem(p);
-  if (rc) return rc;
   WsLayout L;
-  rc = compute_layout(p, &L);
+  int rc = layout_for(p, workspace, &L);
   if (rc) return rc;
   if (L.n_fwd_items == 0) return FCP_OK;
   if (!q || !k || !v || !workspace || (p->n_slot_rows && (!o_part || !lse_part))) { set_error("%s: NULL pointer", who); return FCP_ERR_INVALID_ARG; }
@@ -1589,10 +1591,8 @@ extern "C" int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const
 
 extern "C" int fcp_merge_partials(const fcp_problem* p, const void* o_part, const float* lse_part,
                                   void* o, float* lse, void* workspace, void* stream) {
-  int rc = validate_problem(p);
-  if (rc) return rc;
   WsLayout L;
-  rc = compute_layout(p, &L);
+  int rc = layout_for(p, workspace, &L);
   if (rc) return rc;
   if (L.n_merge_items == 0) return FCP_OK;
   if (!o || !lse || !workspace || (p->n_slots && (!o_part || !lse_part))) { set_error("fcp_merge_partials: NULL pointer"); return FCP_ERR_INVALID_ARG; }
@@ -1610,10 +1610,8 @@ extern "C" int fcp_merge_partials(const fcp_problem* p, const void* o_part, cons
 
 extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const float* lse, const void* d_o,
                                   void* workspace, void* stream) {
-  int rc = validate_problem(p);
-  if (rc) return rc;
   WsLayout L;
-  rc = compute_layout(p, &L);
+  int rc = layout_for(p, workspace, &L);
   if (rc) return rc;
   if (L.t_q == 0) return FCP_OK;
   if (!o || !lse || !d_o || !workspace) { set_error("fcp_bwd_preprocess: NULL pointer"); return FCP_ERR_INVALID_ARG; }
@@ -1630,9 +1628,7 @@ extern "C" int fcp_bwd_preprocess(const fcp_problem* p, const void* o, const flo
 }
 
 static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* workspace) {
-  int rc = validate_problem(p);
-  if (rc) return rc;
-  rc = compute_layout(p, L);
+  int rc = layout_for(p, workspace, L);
   if (rc) return rc;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   a->hdr = reinterpret_cast<WsHeader*>(ws);
