@@ -2,9 +2,12 @@
 """Benchmark of the block-attention hot path on one MI355X.
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM:
-forward partials (fcp_block_attn_fwd_out) -> merge (fcp_merge_partials) -> dQ, which also computes D = rowsum(dO o O)
-(fcp_block_attn_bwd_dq_d) -> dK/dV (fcp_block_attn_bwd_dkdv); the last two are what fcp_block_attn_bwd runs.  The default workload is the
-packed variable-length training step (64K tokens, 1024-token blocks, GQA 32/8, d = 128, bf16).
+forward partials (fcp_block_attn_fwd_out) -> merge (fcp_merge_partials) -> backward.  The backward is what
+fcp_block_attn_bwd runs with FCP_FLAG_BWD_SPILL_DS (the default here): D = rowsum(dO o O) (fcp_bwd_preprocess) -> dK/dV,
+which also leaves dS in the workspace (fcp_block_attn_bwd_dkdv) -> dQ = dS K (fcp_block_attn_bwd_dq_ds); with
+--bwd recompute it is the variant without the flag: dQ kernel that recomputes S and dP and forms D itself
+(fcp_block_attn_bwd_dq_d) -> dK/dV.  The default workload is the packed variable-length training step (64K tokens,
+1024-token blocks, GQA 32/8, d = 128, bf16).
 
 Prints ONE JSON line: whole-step throughput in causal-adjusted TFLOP/s, the roofline of the
 dominant kernel measured with events on the launch stream, and the CPU oracle timed on a
@@ -243,6 +246,9 @@ def main():
     ap.add_argument("--two-step", action="store_true",
                     help="every query block goes through the partial buffers and the merge, also those with one slot")
     ap.add_argument("--bf16-partials", action="store_true", help="keep the partial O buffer in bf16 (FCP_FLAG_PART_BF16)")
+    ap.add_argument("--bwd", choices=("spill", "recompute"), default="spill",
+                    help="backward variant: 'spill' keeps dS in the workspace (FCP_FLAG_BWD_SPILL_DS: D pass, dK/dV kernel that also "
+                         "writes dS, streaming dQ kernel); 'recompute' runs the dQ kernel that recomputes S and dP, with D fused in")
     ap.add_argument("--heads", default=None, metavar="HQ/HKV",
                     help="override the head counts of the workload, e.g. 64/8 (the head shape of the paper's model)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -265,7 +271,8 @@ def main():
         distribute(args)
         return
     import torch
-    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, FCP_FLAG_PART_BF16, fcp_device_info, workloads
+    from paper_2605_08524_amd import (FCP_FLAG_BWD_SPILL_DS, FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, FCP_FLAG_PART_BF16,
+                                      fcp_device_info, workloads)
     from paper_2605_08524_amd.harness import DevicePath
 
     dev = torch.device("cuda:0")
@@ -281,6 +288,9 @@ def main():
     flags = (0 if args.two_step else FCP_FLAG_DIRECT_SINGLE) | (FCP_FLAG_O_F32 if backward else 0)
     if args.bf16_partials:
         flags |= FCP_FLAG_PART_BF16
+    spill = backward and args.bwd == "spill"
+    if spill:
+        flags |= FCP_FLAG_BWD_SPILL_DS
     dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream)
     if args.inputs != "normal":
         for t in (dp.q, dp.k, dp.v) + ((dp.d_o,) if backward else ()):
@@ -291,7 +301,9 @@ def main():
     step_flops = f_fwd + (f_bwd if backward else 0)
 
     stages = [("fwd", dp.fwd), ("merge", dp.merge)]
-    if backward:
+    if backward and spill:
+        stages += [("bwd_pre", dp.bwd_pre), ("bwd_dkdv", dp.bwd_dkdv), ("bwd_dq", dp.bwd_dq_ds)]
+    elif backward:
         stages += [("bwd_dq", dp.bwd_dq_d), ("bwd_dkdv", dp.bwd_dkdv)]
 
     def step(events=None):
@@ -330,8 +342,8 @@ def main():
     # dQ kernel 3 (S, dP, dQ: 6 d; S and dP are recomputed there instead of accumulating dQ with
     # atomics, so the backward executes 14 d per entry for an algorithmic 10 d).
     unit = wl.head_dim * wl.n_q_heads * nnz
-    kernel_flops = {"fwd": 4 * unit, "bwd_dkdv": 8 * unit, "bwd_dq": 6 * unit}
-    kernel_name = {"fwd": "fwd_kernel", "bwd_dkdv": "dkdv_kernel", "bwd_dq": "dq_kernel"}
+    kernel_flops = {"fwd": 4 * unit, "bwd_dkdv": 8 * unit, "bwd_dq": (2 if spill else 6) * unit}
+    kernel_name = {"fwd": "fwd_kernel", "bwd_dkdv": "dkdv_kernel", "bwd_dq": "dq_ds_kernel" if spill else "dq_kernel"}
     cands = [k for k in kernel_flops if k in stage_ms]
     dom = max(cands, key=lambda k: stage_ms[k])
     achieved = kernel_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
@@ -360,6 +372,7 @@ def main():
             "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "n_seqs": int(len(wl.seq_lens)),
             "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
             "nnz_per_head": nnz, "o_dtype": "f32" if backward else "bf16", "parallelism": "single-gpu",
+            "backward": (args.bwd if backward else None), "workspace_bytes": dp.ws_bytes,
         },
         "frac_of_bf16_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},

@@ -60,6 +60,14 @@ enum {
                                     A final O merged from bf16 partials carries bf16 rounding whatever its own dtype:
                                     meant for forward-only use (the backward's D = rowsum(dO o O) inherits it). */
   FCP_FLAG_GRAD_BF16 = 8,        /* the backward writes dq, dk, dv as bf16 instead of fp32 */
+  FCP_FLAG_BWD_SPILL_DS = 16,    /* the backward keeps dS (bf16, scale folded in) of every visible 32x32 score tile in the
+                                    workspace: the dK/dV kernel, which computes it anyway, writes it, and dQ = dS K is then
+                                    one streaming contraction (fcp_block_attn_bwd_dq_ds) instead of a second kernel that
+                                    recomputes S and dP.  Costs 2 bytes of workspace per unmasked score entry and query head
+                                    (rounded up to 32x32 tiles; fcp_workspace_bytes accounts for it) and trades two of the
+                                    backward's seven executed contractions for that much HBM traffic each way.  Set it
+                                    before fcp_workspace_bytes / fcp_queue_build and keep it for every call on the
+                                    workspace.  Shares whose dS does not fit in memory leave it unset. */
   FCP_FLAG_DIRECT_SINGLE = 2     /* a query block with ONE slot needs no reduction: fcp_block_attn_fwd_out writes its
                                     result straight to the final o / lse and fcp_merge_partials leaves it alone.
                                     Set it before fcp_workspace_bytes / fcp_queue_build and keep it for every call
@@ -236,6 +244,18 @@ int fcp_block_attn_bwd_dq(const fcp_problem* p, const void* q, const void* k, co
 int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, const void* k, const void* v,
                             const void* o, const float* lse, const void* d_o, void* dq,
                             void* workspace, void* stream);
+
+/*
+ * fcp_block_attn_bwd_dq_ds -- dQ from the dS that fcp_block_attn_bwd_dkdv left in the workspace (FCP_FLAG_BWD_SPILL_DS).
+ *
+ * dQ[i, h, :] = sum_j dS[i, j] K[j, :] over the visible keys j of row i, with dS = P o (dP - D) * scale as the dK/dV
+ * kernel formed and rounded it (same backward definition as fcp_block_attn_bwd).  Needs fcp_block_attn_bwd_dkdv to
+ * have run on the same workspace with the flag set (same stream, or ordered after it).  k: device bf16 [T_kv,Hkv,d];
+ * dq: device [T_q,Hq,d] fp32 (bf16 with FCP_FLAG_GRAD_BF16), fully overwritten, one writer per row.
+ * Errors: FCP_ERR_INVALID_ARG when the flag is not set or a pointer is NULL; otherwise as fcp_block_attn_bwd.
+ * With the flag, fcp_block_attn_bwd = fcp_bwd_preprocess, fcp_block_attn_bwd_dkdv, then this call.
+ */
+int fcp_block_attn_bwd_dq_ds(const fcp_problem* p, const void* k, void* dq, void* workspace, void* stream);
 
 /* Text of the calling thread's last error ("" if none).  The pointer stays valid until the
  * thread's next failing call. */

@@ -28,11 +28,12 @@ FCP_FLAG_O_F32 = 1
 FCP_FLAG_DIRECT_SINGLE = 2
 FCP_FLAG_PART_BF16 = 4
 FCP_FLAG_GRAD_BF16 = 8
+FCP_FLAG_BWD_SPILL_DS = 16
 
 EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
-    "fcp_block_attn_bwd_dq_d", "fcp_block_attn_fwd_static",
+    "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_block_attn_fwd_static",
     "fcp_last_error", "fcp_device_info", "fcp_mfma_probe",
     "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
     "fcp_coalesce_stages", "fcp_pack_units",
@@ -82,6 +83,7 @@ def _load():
     lib.fcp_block_attn_bwd_dkdv.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 8
     lib.fcp_block_attn_bwd_dq.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
     lib.fcp_block_attn_bwd_dq_d.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 9
+    lib.fcp_block_attn_bwd_dq_ds.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 4
     i64p = C.POINTER(C.c_int64)
     lib.fcp_block_costs.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, i32p]
     lib.fcp_pack_units.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, i32p]
@@ -229,6 +231,10 @@ def fcp_block_attn_bwd_dq(problem: Problem, q, k, v, d_o, dq, workspace, stream=
 def fcp_block_attn_bwd_dq_d(problem: Problem, q, k, v, o, lse, d_o, dq, workspace, stream=None):
     _check(_lib.fcp_block_attn_bwd_dq_d(problem.ref, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq),
                                         _ptr(workspace), _stream(stream)))
+
+
+def fcp_block_attn_bwd_dq_ds(problem: Problem, k, dq, workspace, stream=None):
+    _check(_lib.fcp_block_attn_bwd_dq_ds(problem.ref, _ptr(k), _ptr(dq), _ptr(workspace), _stream(stream)))
 
 
 def fcp_device_info():

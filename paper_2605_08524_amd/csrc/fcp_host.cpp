@@ -155,6 +155,17 @@ int compute_layout(const fcp_problem* p, WsLayout* L) {
   // backward scratch, head-major [Hq][T_q] fp32: D * scale, then LSE * log2(e)
   L->off_dls = off;         off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
   L->off_lse2 = off;        off = align(off + sizeof(float) * (size_t)std::max<int64_t>(1, L->t_q * p->n_q_heads));
+  L->off_ds = off;
+  if (p->flags & FCP_FLAG_BWD_SPILL_DS) {
+    int64_t frags = kDsSinkFrags;
+    for (int i = 0; i < p->n_pairs; i++)
+      frags += p->n_q_heads * ds_frags_per_head(p->pairs[i].kind, p->q_blocks[p->pairs[i].q_blk].tok_len,
+                                                p->kv_blocks[p->pairs[i].kv_blk].tok_len);
+    frags += 1;   // the dQ kernel requests fragments in pairs: one past the last may be named (never used)
+    if (frags > INT32_MAX) { set_error("FCP_FLAG_BWD_SPILL_DS: more than 2^31-1 dS fragments"); return FCP_ERR_UNSUPPORTED; }
+    L->n_ds_frags = frags;
+    off = align(off + (size_t)frags * kDsFragBytes);
+  }
   L->total = off;
   return FCP_OK;
 }
@@ -171,7 +182,7 @@ struct LayoutKey {
   bool operator==(const LayoutKey& o) const { return workspace == o.workspace && std::memcmp(v, o.v, sizeof(v)) == 0; }
 };
 LayoutKey make_key(const fcp_problem* p, const void* ws) {
-  return LayoutKey{ws, {p->n_q_heads, p->n_kv_heads, p->head_dim, p->block_size, p->flags & FCP_FLAG_DIRECT_SINGLE,
+  return LayoutKey{ws, {p->n_q_heads, p->n_kv_heads, p->head_dim, p->block_size, p->flags & (FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_BWD_SPILL_DS),
                         p->n_kv_blocks, p->n_q_blocks, p->n_pairs, p->n_slots, p->n_slot_rows, 0}};
 }
 constexpr int kLayoutCacheSize = 32;
@@ -203,6 +214,17 @@ int layout_for(const fcp_problem* p, const void* workspace, WsLayout* L) {
 }
 
 namespace {
+
+// 64-row KV tiles that a query-stationary item visits: every pair in full, a DIAG pair up to the item's last row.
+void count_tiles(QItem* it, const DevPair* dpairs) {
+  const int row_hi = std::max(it->tile_off[0] + it->q_rows[0], it->tile_off[1] + it->q_rows[1]);
+  int n = 0;
+  for (int i = it->pair_begin; i < it->pair_begin + it->n_pairs; i++) {
+    const int nc = dpairs[i].kind == FCP_KIND_DIAG ? std::min(dpairs[i].kv_len, row_hi) : dpairs[i].kv_len;
+    n += (nc + kQTileN - 1) / kQTileN;
+  }
+  it->n_tiles = n;
+}
 
 // Longest-processing-time assignment of weighted groups to the XCD queues: groups in
 // descending weight, each to the currently lightest queue.  Ties resolve to the lower index.
@@ -361,9 +383,14 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
   WsHeader* hdr = reinterpret_cast<WsHeader*>(host.data());
   for (float& x : hdr->infs) x = INFINITY;
   DevPair* dpairs = reinterpret_cast<DevPair*>(host.data() + L.off_pairs);
-  for (int i = 0; i < p->n_pairs; i++) {
-    const fcp_block& kb = p->kv_blocks[p->pairs[i].kv_blk];
-    dpairs[i] = {kb.tok_start, kb.tok_len, p->pairs[i].kind, 0};
+  {
+    const bool spill = (p->flags & FCP_FLAG_BWD_SPILL_DS) != 0;
+    int64_t frag = kDsSinkFrags;
+    for (int i = 0; i < p->n_pairs; i++) {
+      const fcp_block& kb = p->kv_blocks[p->pairs[i].kv_blk];
+      dpairs[i] = {kb.tok_start, kb.tok_len, p->pairs[i].kind, spill ? (int32_t)frag : 0};
+      frag += p->n_q_heads * ds_frags_per_head(p->pairs[i].kind, p->q_blocks[p->pairs[i].q_blk].tok_len, kb.tok_len);
+    }
   }
   const int G = p->n_q_heads / p->n_kv_heads;
   // ---- forward: one group per (slot, KV head): its items share K/V.  An item joins two sub-tiles:
@@ -401,8 +428,9 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
           for (int t = n_tiles - 1; t >= 0; t--)         // later tiles of a DIAG pair are heavier
             for (int hh = 0; hh < G; hh += 2) {
               QItem it{};
-              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.pad[0] = to_final;
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.to_final = to_final;
               sub(&it, 0, t, g * G + hh); sub(&it, 1, t, g * G + hh + 1);
+              count_tiles(&it, dpairs);
               items.push_back(it);
               w += 2 * tile_w[t];
             }
@@ -410,10 +438,11 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
           for (int t = n_tiles - 1; t >= 0; t -= 2)
             for (int hh = 0; hh < G; hh++) {
               QItem it{};
-              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.pad[0] = to_final;
+              it.pair_begin = sl.pair_begin; it.n_pairs = sl.n_pairs; it.to_final = to_final;
               sub(&it, 0, t, g * G + hh);
               if (t >= 1) { sub(&it, 1, t - 1, g * G + hh); w += tile_w[t - 1]; }
               else { it.q_start[1] = it.q_start[0]; it.q_rows[1] = 0; it.out_row[1] = it.out_row[0]; it.tile_off[1] = it.tile_off[0]; it.head[1] = it.head[0]; }
+              count_tiles(&it, dpairs);
               items.push_back(it);
               w += tile_w[t];
             }
@@ -437,7 +466,7 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
     BwdDep* deps = reinterpret_cast<BwdDep*>(host.data() + L.off_bwd_deps);
     for (int i = 0; i < p->n_pairs; i++) {           // pairs are visited in q order -> deps ascend in q
       const fcp_block& qb = p->q_blocks[p->pairs[i].q_blk];
-      deps[cursor[p->pairs[i].kv_blk]++] = {qb.tok_start, qb.tok_len, p->pairs[i].kind, 0};
+      deps[cursor[p->pairs[i].kv_blk]++] = {qb.tok_start, qb.tok_len, p->pairs[i].kind, dpairs[i].ds_frag};
     }
     // The DIAG dependency goes last: the tiles of one KV block then walk the FULL dependencies in
     // lockstep (identical step sequences, same XCD), so the Q / dO stream they share stays in L2;
@@ -466,7 +495,7 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
         int64_t w = 0;
         for (int t = 0; t < n_tiles; t++) {            // earlier tiles of a DIAG pair are heavier
           const int off = t * kBwdTileN;
-          items.push_back({kb.tok_start + off, std::min(kBwdTileN, kb.tok_len - off), off, d0, nd, g, 0, 0});
+          items.push_back({kb.tok_start + off, std::min(kBwdTileN, kb.tok_len - off), off, d0, nd, g, kb.tok_len, 0});
           w += tile_w[t];
         }
         groups.push_back(std::move(items));
@@ -515,8 +544,9 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
           for (int t = n_tiles - 1; t >= 0; t--)
             for (int hh = 0; hh < G; hh += 2) {
               QItem it{};
-              it.pair_begin = pb[b]; it.n_pairs = pn[b];
+              it.pair_begin = pb[b]; it.n_pairs = pn[b]; it.q_blk_len = qb.tok_len;
               sub(&it, 0, t, g * G + hh); sub(&it, 1, t, g * G + hh + 1);
+              count_tiles(&it, dpairs);
               items.push_back(it);
               w += 2 * tile_w[t];
             }
@@ -524,10 +554,11 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
           for (int t = n_tiles - 1; t >= 0; t -= 2)
             for (int hh = 0; hh < G; hh++) {
               QItem it{};
-              it.pair_begin = pb[b]; it.n_pairs = pn[b];
+              it.pair_begin = pb[b]; it.n_pairs = pn[b]; it.q_blk_len = qb.tok_len;
               sub(&it, 0, t, g * G + hh);
               if (t >= 1) { sub(&it, 1, t - 1, g * G + hh); w += tile_w[t - 1]; }
               else { it.q_start[1] = it.q_start[0]; it.q_rows[1] = 0; it.out_row[1] = it.out_row[0]; it.tile_off[1] = it.tile_off[0]; it.head[1] = it.head[0]; }
+              count_tiles(&it, dpairs);
               items.push_back(it);
               w += tile_w[t];
             }

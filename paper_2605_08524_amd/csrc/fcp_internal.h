@@ -18,13 +18,29 @@ constexpr int kMergeChunk = 1024;   // most (row, head) entries per merge work i
 constexpr int kMergeMinItems = 2048;  // the merge aims at this many work items at least: 8 per compute unit
 
 // Device-side records (all int32 so the host can build them as plain arrays).
-struct DevPair { int32_t kv_start, kv_len, kind, pad; };
+// ds_frag: first 32x32 dS fragment of the pair in the spill buffer (FCP_FLAG_BWD_SPILL_DS; else 0).
+struct DevPair { int32_t kv_start, kv_len, kind, ds_frag; };
 // Query-stationary item of two 128-row sub-tiles that walk the same pair list and share a KV head
 // (two query heads of a group, or two neighbouring row tiles of one head; q_rows[1] = 0: none).
-// pad[0] != 0 (forward items only): the slot is the only one of its query block.
-struct QItem { int32_t q_start[2], q_rows[2], out_row[2], tile_off[2], head[2], pair_begin, n_pairs, pad[4]; };
-struct BwdDep  { int32_t q_start, q_len, kind, pad; };
-struct BwdItem { int32_t kv_start, kv_rows, tile_off, dep_begin, n_deps, kv_head, pad0, pad1; };
+// to_final != 0 (forward items only): the slot is the only one of its query block.
+// q_blk_len (dQ items only): rows of the whole query block.
+// n_tiles: 64-row KV tiles the item walks (a DIAG pair only up to the item's last query row).
+struct QItem { int32_t q_start[2], q_rows[2], out_row[2], tile_off[2], head[2], pair_begin, n_pairs, to_final, q_blk_len, n_tiles, pad; };
+constexpr int kQTileN = 64;         // KV rows per LDS tile of the query-stationary kernels
+struct BwdDep  { int32_t q_start, q_len, kind, ds_frag; };
+struct BwdItem { int32_t kv_start, kv_rows, tile_off, dep_begin, n_deps, kv_head, kv_blk_len, pad1; };
+
+// The dS spill buffer (FCP_FLAG_BWD_SPILL_DS) is a sequence of 2 KB fragments, one per (pair, query head,
+// 32 query rows, 32 KV rows).  Fragments [0, kDsSinkFrags) take the stores of steps that have no fragment
+// (pipeline fill, tiles above the diagonal); a pair's fragments follow from its ds_frag, head-major, then by
+// 32-row query group; a FULL pair keeps ceil(kv_len / 32) fragments per query group, a DIAG pair only those at or
+// below the diagonal (query group i keeps i + 1).
+constexpr int kDsFragBytes = 2048;
+constexpr int kDsSinkFrags = 256;
+inline int64_t ds_frags_per_head(int kind, int q_len, int kv_len) {
+  const int64_t nq = (q_len + 31) / 32, nk = (kv_len + 31) / 32;
+  return kind == FCP_KIND_DIAG ? nq * (nq + 1) / 2 : nq * nk;
+}
 struct MergeItem { int32_t out_rh, n_rh, slot_begin, n_slots, rh_off, pad0, pad1, pad2; };
 
 // Header at the start of the workspace.  Counters are zero between launches: the last
@@ -49,7 +65,8 @@ struct WsLayout {
   int64_t n_fwd_items, n_bwd_items, n_bwd_deps, n_merge_items, n_dq_items, t_q, t_kv;
   int fwd_tile_m;   // query rows per forward item, chosen per problem
   int merge_chunk;  // (row, head) entries per merge work item, chosen per problem
-  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_dls, off_lse2, total;
+  int64_t n_ds_frags;   // fragments of the dS spill buffer, sinks and one fragment of slack included (0 without the flag)
+  size_t off_pairs, off_fwd_items, off_bwd_deps, off_bwd_items, off_merge_items, off_slot_rh, off_dq_items, off_dls, off_lse2, off_ds, total;
 };
 
 int validate_problem(const fcp_problem* p);           // host; sets the error text

@@ -216,6 +216,33 @@ __device__ __forceinline__ void retire(int32_t* counter, int32_t* done) {
   }
 }
 
+// The item sequence of one persistent workgroup of a query-stationary kernel.  The index of the NEXT item is
+// requested when the current one starts (one atomic add on the home queue by thread 0, not waited for) and
+// published through LDS when the current one ends, so the round trip to the counter overlaps the item's work
+// instead of sitting between two items.  Once the home queue runs dry the slower pop_item (which also steals
+// from the other queues) takes over; every workgroup leaves the loop when all queues are dry.
+struct ItemStream {
+  int32_t* counter; const int32_t* begin;
+  int home, home_n, home_begin, ticket;
+  bool home_dry;
+  __device__ __forceinline__ void init(int32_t* c, const int32_t* b) {
+    counter = c; begin = b;
+    home = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kNumXcd - 1);
+    home_begin = b[home]; home_n = b[home + 1] - home_begin;
+    home_dry = home_n <= 0; ticket = 0;
+  }
+  // thread 0 only: ask for the next item (returns at once; the ticket arrives while the item runs)
+  __device__ __forceinline__ void request() { if (!home_dry) ticket = atomicAdd(&counter[home], 1); }
+  // thread 0 only: the item the ticket stands for, or one stolen elsewhere, or -1
+  __device__ __forceinline__ int resolve() {
+    if (!home_dry) {
+      if (ticket < home_n) return home_begin + ticket;
+      home_dry = true;
+    }
+    return pop_item(counter, begin);
+  }
+};
+
 // =====================================================================================
 // Forward: partial attention.  Item = (slot, two 128-row query sub-tiles that share the slot's
 // K/V stream: two query heads of one KV head, or two neighbouring row tiles of one head);
@@ -231,7 +258,7 @@ __device__ __forceinline__ void retire(int32_t* counter, int32_t* done) {
 // and the last one only adds the last tile to O, so the pipeline fill costs no MFMAs; all
 // iterations issue the same tile loads, and the ring runs on from item to item.
 // =====================================================================================
-constexpr int kFwdTileN = 64;   // KV rows per LDS tile
+constexpr int kFwdTileN = kQTileN;   // KV rows per LDS tile (the host counts an item's tiles with the same constant)
 constexpr int kFwdBufs = 4;     // ring of [K | V] tile buffers
 constexpr float kRescaleSlack = 8.0f;   // log2 units
 
@@ -252,7 +279,11 @@ struct TileIter {
   DevPair cur;
   bool more;
   __device__ __forceinline__ void load_pair() {
-    cur = pairs[pair];
+    // the pair index is wave-uniform; readfirstlane says so to the compiler, which then keeps the record (and
+    // everything derived from it) in scalar registers and branches on it with scalar branches
+    const DevPair p = pairs[pair];
+    cur.kv_start = __builtin_amdgcn_readfirstlane(p.kv_start); cur.kv_len = __builtin_amdgcn_readfirstlane(p.kv_len);
+    cur.kind = __builtin_amdgcn_readfirstlane(p.kind); cur.ds_frag = __builtin_amdgcn_readfirstlane(p.ds_frag);
     ncols = cur.kind == FCP_KIND_DIAG ? min(cur.kv_len, row_hi) : cur.kv_len;
   }
   __device__ __forceinline__ void init(const DevPair* p, int begin, int n, int row_hi_) {
@@ -327,11 +358,13 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
   for (int kc = 0; kc < KC; kc++) kk_off[kc] = lds_addr(lds_kv[b_k]) + tile_off<D>(l32, 2 * kc + g);
   __syncthreads();
 
+  ItemStream items;
+  if (tid == 0) { items.init(a.hdr->fwd_counter, a.hdr->fwd_begin); items.request(); s_item = items.resolve(); }
+  __syncthreads();
   for (;;) {
-    if (tid == 0) s_item = pop_item(a.hdr->fwd_counter, a.hdr->fwd_begin);
-    __syncthreads();
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
+    if (tid == 0) items.request();      // the item after this one
     const QItem it = a.items[item_idx];
     // selects, not it.q_rows[sub]: a run-time index would put the whole item into private memory
     const int q_rows = (sub ? it.q_rows[1] : it.q_rows[0]), tile_off_q = (sub ? it.tile_off[1] : it.tile_off[0]), head = (sub ? it.head[1] : it.head[0]);
@@ -364,12 +397,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     // number of tiles of the item, and of iterations: tiles + 1 (pipeline fill)
     TileIter ti;                      // names the next tile to LOAD
     ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
-    int n_it = 1;
-    for (int p = 0; p < it.n_pairs; p++) {
-      const DevPair pr = a.pairs[it.pair_begin + p];
-      const int nc = pr.kind == FCP_KIND_DIAG ? min(pr.kv_len, ti.row_hi) : pr.kv_len;
-      n_it += (nc + kFwdTileN - 1) / kFwdTileN;
-    }
+    const int n_it = 1 + it.n_tiles;
 
     // The load of one tile in two parts.  describe(): scalar bookkeeping with branches, run at
     // an iteration boundary.  issue(): branch-free, sits between the MFMAs.
@@ -564,7 +592,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (row_ok) {
       // the only slot of its query block: this is the final result, not a partial
-      const bool to_final = it.pad[0] != 0;
+      const bool to_final = it.to_final != 0;
       const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
       const int64_t off = row * q_row_stride + (int64_t)head * D;
       if (to_final ? !a.o_is_f32 : a.part_is_bf16) {
@@ -586,7 +614,9 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         (to_final ? a.lse : a.lse_part)[row * a.n_q_heads + head] = lse;
       }
     }
-    __syncthreads();   // s_item is rewritten next
+    __syncthreads();   // every wave has read s_item
+    if (tid == 0) s_item = items.resolve();
+    __syncthreads();
   }
   if (tid == 0) retire(a.hdr->fwd_counter, &a.hdr->fwd_done);
 }
@@ -780,6 +810,7 @@ struct BwdArgs {
   // dq_kernel<D, true, *> computes those two itself from O, LSE and dO and writes them for dkdv_kernel
   const void* o; const float* lse; int32_t o_is_f32; float* lse2_out; float* dls_out;
   void* dq; void* dk; void* dv;    // fp32, or bf16 in the GRAD_BF16 instances of the kernels
+  unsigned char* ds;               // dS spill buffer (2 KB fragments), or NULL
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
   int64_t t_q;
   int32_t n_q_heads, n_kv_heads;
@@ -818,7 +849,7 @@ struct StepIter {
 constexpr int kDkdvBufs = 7;        // ring of LDS step buffers
 constexpr int kNoMask = 1 << 30;    // diagonal threshold of a step that needs no mask
 
-template <int D, bool GRAD_BF16>
+template <int D, bool GRAD_BF16, bool SPILL>
 __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
@@ -1027,7 +1058,22 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
       }
     } else {
       // =============================== producer ===============================
-      const int kvg = it.tile_off + my_kv - 4 * g;       // masked iff kvg > q0 + 8*(r/4) + r%4 on a DIAG step
+      int kvg = it.tile_off + my_kv - 4 * g;       // masked iff kvg > q0 + 8*(r/4) + r%4 on a DIAG step
+      // SPILL: the dS this wave forms also goes to memory, one 2 KB fragment per step, for the dQ pass.  There a
+      // KV row past the ragged end of the tile must carry dS = 0 (here its column of dK^T / dV^T is simply never
+      // stored): such lanes get a threshold nothing passes, and a ragged tile runs every step through the masked
+      // variant.  Fragment layout, shared with dq_ds_kernel: the 16 bytes that lane (KV row r = lane % 32,
+      // g = lane / 32) holds for j = 0, 1 (query rows 16j + 4g + {0..3} and 16j + 8 + 4g + {0..3} of the step)
+      // sit at byte 1024 j + 512 g + 16 ((r + 8 j + 4 g) % 32): every store instruction writes 1 KB of consecutive
+      // memory, and the rotation makes the transposing LDS reads of the dQ pass bank-conflict free.
+      if constexpr (SPILL) { if (!kv_ok) kvg = 0x7fff0000; }
+      const int thr_none = (SPILL && it.kv_rows < kBwdTileN) ? kNoMask - 1 : kNoMask;
+      const int nkv32 = (it.kv_blk_len + 31) >> 5, my_kv32 = (it.tile_off >> 5) + sub;
+      const int sink = (int)(blockIdx.x & (kDsSinkFrags - 1));
+      int frag_t = sink;         // fragment of the step that B handles in this interval
+      uint32_t sp_off[2];
+#pragma unroll
+      for (int j = 0; j < 2; j++) sp_off[j] = 1024 * j + 512 * g + 16 * ((l32 + 8 * j + 4 * g) & 31);
       // B operands of S and dP: this pair's K and V rows; lane = KV row, 8 consecutive d per k-chunk.
       bf16x8 kf[KC], vf[KC];
       {
@@ -1046,7 +1092,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 #pragma unroll
       for (int kc = 0; kc < KC; kc++) row_a[kc] = lds_addr(lds_t[0]) + b_p * BUF + tile_off<D>(l32, 2 * kc + g);
       uint32_t sc_a = lds_sc0 + b_s * 256 + 16 * g;      // scalars of step i+1: rows 8*q4 + 4g .. +3 at +32*q4, D*scale at +128
-      int thr_t = kNoMask;       // diagonal threshold of the step that B handles in this interval
+      int thr_t = thr_none;      // diagonal threshold of the step that B handles in this interval
       f32x16 s_a, dp_a, s_b, dp_b;
 #pragma unroll
       for (int r = 0; r < 16; r++) { s_a[r] = 0.f; dp_a[r] = 0.f; s_b[r] = 0.f; dp_b[r] = 0.f; }
@@ -1066,6 +1112,8 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         uint32_t pk[16];           // [0..7] P pairs, [8..15] dS pairs: four B operands for the consumer
         float p_prev = 0.f, ds_prev = 0.f;
         const uint32_t hdst = lds_h0 + (hb ^ 1) * (4 * 4096);
+        unsigned char* fptr = nullptr;
+        if constexpr (SPILL) fptr = a.ds + (int64_t)__builtin_amdgcn_readfirstlane(frag_t) * kDsFragBytes;
         float p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0], a.scale_log2, -lse_c[0]));
 #pragma unroll
         for (int k = 0; k < NS; k++) {
@@ -1125,14 +1173,36 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
               const u32x4 wd = {pk[8 + 4 * j], pk[8 + 4 * j + 1], pk[8 + 4 * j + 2], pk[8 + 4 * j + 3]};
               *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(hdst + j * 1024) = wp;
               *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(hdst + (2 + j) * 1024) = wd;
+              if constexpr (SPILL) *reinterpret_cast<u32x4*>(fptr + sp_off[j]) = wd;
             }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
+        if constexpr (SPILL) {
+          // the hand-over writes must have landed; the fragment stores need not (a full fence would wait for them)
+          __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+          asm volatile("s_barrier" ::: "memory");
+        } else {
+          __syncthreads();
+        }
         // the step that B handles next
-        thr_t = kNoMask;
-        if (si.more) { if (si.cur.kind == FCP_KIND_DIAG) thr_t = si.q0; si.advance(); }
+        thr_t = thr_none;
+        if constexpr (SPILL) frag_t = sink;
+        if (si.more) {
+          if (si.cur.kind == FCP_KIND_DIAG) thr_t = si.q0;
+          if constexpr (SPILL) {
+            const int q32 = si.q0 >> 5, nq32 = (si.cur.q_len + 31) >> 5;
+            const int head = it.kv_head * group + si.hh;
+            if (sub * 32 < it.kv_rows) {
+              if (si.cur.kind == FCP_KIND_DIAG) {
+                if (my_kv32 <= q32) frag_t = si.cur.ds_frag + head * (nq32 * (nq32 + 1) / 2) + q32 * (q32 + 1) / 2 + my_kv32;
+              } else {
+                frag_t = si.cur.ds_frag + (head * nq32 + q32) * nkv32 + my_kv32;
+              }
+            }
+          }
+          si.advance();
+        }
         hb ^= 1;
       };
       // the first interval handles B(-1) (nothing) and A(0), the second B(0) and A(1), ...
@@ -1195,11 +1265,13 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
     buf ^= 1;
   };
 
+  ItemStream items;
+  if (tid == 0) { items.init(a.hdr->dq_counter, a.hdr->dq_begin); items.request(); s_item = items.resolve(); }
+  __syncthreads();
   for (;;) {
-    if (tid == 0) s_item = pop_item(a.hdr->dq_counter, a.hdr->dq_begin);
-    __syncthreads();
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
     if (item_idx < 0) break;
+    if (tid == 0) items.request();      // the item after this one
     const QItem it = a.dq_items[item_idx];
     const int q_start = (sub ? it.q_start[1] : it.q_start[0]), q_rows = (sub ? it.q_rows[1] : it.q_rows[0]), tile_off_q = (sub ? it.tile_off[1] : it.tile_off[0]), head = (sub ? it.head[1] : it.head[0]);
     const int kvh = it.head[0] / group;
@@ -1385,6 +1457,202 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
           }
       }
     }
+    __syncthreads();   // every wave has read s_item
+    if (tid == 0) s_item = items.resolve();
+    __syncthreads();
+  }
+  if (tid == 0) retire(a.hdr->dq_counter, &a.hdr->dq_done);
+}
+
+// =====================================================================================
+// Backward, part 2 without recomputation -- dQ from the dS fragments that dkdv_kernel<.., SPILL> left in memory.
+// Same items as dq_kernel (two 128-row query sub-tiles that share a KV head, over all pairs of the query block);
+// 8 waves, wave = (sub-item, 32-row query group).  Per 64-row KV tile:
+//   dQ^T (d x 32 query rows) += K^T (d x 64) dS^T (64 x 32)
+// A = K^T by transpose reads of the shared K tile; B = dS^T by transpose reads of the wave's own two fragments,
+// which hold dS^T[kv][q] in the 8-byte pieces the producer wrote (4 consecutive query rows of one KV row) at
+// rotated positions (see dkdv_kernel), so that a half-wave's 32 pieces cover the 64 banks once.  Both operands
+// assign the 8 k-slots of lane half g to KV rows {4g..4g+3} and {8+4g..8+4g+3} of the 16-row chunk.
+// The kernel is bound by the HBM stream of fragments (2 bytes per score entry and head against 2 d FLOPs), so the
+// ring of three stages (K tile + 8 x 2 fragments each) is there to keep two stages of loads in flight, filled by
+// LDS-DMA; one workgroup barrier per tile.  Nothing is masked here: dS is already zero wherever a score is masked,
+// and fragments above a wave's diagonal or past a ragged end are skipped, not read.
+// =====================================================================================
+constexpr int kDqDsBufs = 3;
+
+template <int D, bool GRAD_BF16>
+__global__ void __launch_bounds__(512, 2) dq_ds_kernel(BwdArgs a) {
+  constexpr int DT = D / 32;
+  constexpr int TBK = tile_bytes<D>(kFwdTileN);
+  constexpr int WDS = 2 * kDsFragBytes;               // a wave's two fragments of a tile
+  constexpr int STAGE = TBK + 8 * WDS;
+  constexpr int NB = kDqDsBufs;
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NDMA = kFwdTileN / RPI / 8;
+  constexpr int DMA_PER_TILE = NDMA + WDS / 1024;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_st[NB][STAGE];
+  __shared__ int s_item;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int sub = wave >> 2, wq = wave & 3;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int64_t q_row_stride = (int64_t)a.n_q_heads * D;
+  const int64_t kv_row_stride = (int64_t)a.n_kv_heads * D;
+  const unsigned char* zeros = reinterpret_cast<const unsigned char*>(a.hdr->zeros);
+  // K tile loads: as in the forward (rows past a ragged end repeat the last valid row: their dS is zero)
+  uint32_t dma_row[NDMA], dma_chunk[NDMA];
+#pragma unroll
+  for (int n = 0; n < NDMA; n++) {
+    const int r = (8 * n + wave) * RPI + lane / CPR, pc = lane % CPR;
+    dma_row[n] = (uint32_t)(r * kv_row_stride * 2);
+    dma_chunk[n] = (uint32_t)((pc ^ swz<D>(r)) << 4);
+  }
+  // K^T operands: transpose reads of the K tile, d rows 32 dt .. of k-chunk rows {4g..} / {8+4g..}
+  const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  uint32_t tr_lo[DT], tr_hi[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++) {
+    tr_lo[dt] = lds_addr(lds_st[0]) + tile_off<D>(4 * g + tr_row, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+    tr_hi[dt] = lds_addr(lds_st[0]) + tile_off<D>(4 * g + tr_row + 8, 4 * dt + (tr_col >> 3)) + (tr_col & 4) * 2;
+  }
+  // dS^T operands: lane s of a 16-lane group names the piece of KV row r0 + s / 4, query columns 16 (G & 1) + 4 (s & 3) ..
+  uint32_t ds_a[2][2];      // [k-chunk of the fragment][rows +0..3 / +8..11]
+  {
+    const int s16 = lane & 15, G = lane >> 4;
+    const int j = G & 1, gg = s16 & 1, mm = (s16 >> 1) & 1;
+#pragma unroll
+    for (int kc = 0; kc < 2; kc++)
+#pragma unroll
+      for (int h = 0; h < 2; h++) {
+        const int r = 16 * kc + 8 * h + 4 * g + (s16 >> 2);
+        ds_a[kc][h] = lds_addr(lds_st[0]) + TBK + wave * WDS + 1024 * j + 512 * gg + 16 * ((r + 8 * j + 4 * gg) & 31) + 8 * mm;
+      }
+  }
+  int b_c = 0, b_dma = 0;       // ring positions: stage being read, stage being filled
+  auto advance_read_stage = [&]() {
+    const int st = (b_c == NB - 1) ? -(NB - 1) * STAGE : STAGE;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) { tr_lo[dt] += st; tr_hi[dt] += st; }
+#pragma unroll
+    for (int kc = 0; kc < 2; kc++) { ds_a[kc][0] += st; ds_a[kc][1] += st; }
+    b_c = (b_c == NB - 1) ? 0 : b_c + 1;
+  };
+
+  ItemStream items;
+  if (tid == 0) { items.init(a.hdr->dq_counter, a.hdr->dq_begin); items.request(); s_item = items.resolve(); }
+  __syncthreads();
+  for (;;) {
+    const int item_idx = __builtin_amdgcn_readfirstlane(s_item);
+    if (item_idx < 0) break;
+    if (tid == 0) items.request();      // the item after this one
+    const QItem it = a.dq_items[item_idx];
+    const int q_start = (sub ? it.q_start[1] : it.q_start[0]), q_rows = (sub ? it.q_rows[1] : it.q_rows[0]), tile_off_q = (sub ? it.tile_off[1] : it.tile_off[0]), head = (sub ? it.head[1] : it.head[0]);
+    const int kvh = it.head[0] / group;
+    const int my_row = wq * 32 + l32;
+    const bool row_ok = my_row < q_rows;
+    const int wave_row_lo = tile_off_q + wq * 32;
+    const bool wave_ok = wq * 32 < q_rows;                       // the wave has at least one valid row
+    const int nq32 = (it.q_blk_len + 31) >> 5;
+    const int q32 = min((tile_off_q >> 5) + wq, nq32 - 1);       // clamped: a wave past the ragged end reads valid memory and uses nothing
+    const uint16_t* kbase = a.k + (int64_t)kvh * D;
+
+    f32x16 acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
+
+    TileIter ti;
+    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
+    const int n_tiles = it.n_tiles;
+    // The load of one tile: describe() = scalar bookkeeping, issue() = branch-free requests.
+    uint64_t d_k = 0, d_ds = 0;
+    uint32_t d_lim = 0;
+    int d_vis = 0;                  // columns of the tile that this wave's rows can see (0 .. 64)
+    auto describe = [&]() {
+      d_k = reinterpret_cast<uint64_t>(zeros); d_lim = 0; d_vis = 0;
+      d_ds = reinterpret_cast<uint64_t>(a.ds);
+      if (ti.more) {
+        const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
+        d_k = reinterpret_cast<uint64_t>(kbase + row0);
+        const int valid = min(kFwdTileN, ti.cur.kv_len - ti.c0);
+        d_lim = (uint32_t)((valid - 1) * kv_row_stride * 2);
+        const int f0 = ti.c0 >> 5;
+        int frag;
+        if (ti.cur.kind == FCP_KIND_DIAG) {
+          frag = ti.cur.ds_frag + head * (nq32 * (nq32 + 1) / 2) + q32 * (q32 + 1) / 2 + min(f0, q32);
+        } else {
+          const int nkv32 = (ti.cur.kv_len + 31) >> 5;
+          frag = ti.cur.ds_frag + (head * nq32 + q32) * nkv32 + min(f0, nkv32 - 1);
+        }
+        d_ds = reinterpret_cast<uint64_t>(a.ds + (int64_t)frag * kDsFragBytes);
+        const int vis = ti.cur.kind == FCP_KIND_DIAG ? min(ti.cur.kv_len, wave_row_lo + 32) : ti.cur.kv_len;
+        d_vis = wave_ok ? max(0, min(kFwdTileN, vis - ti.c0)) : 0;
+        ti.advance();
+      }
+    };
+    auto issue = [&]() {
+      const uint32_t lbase = lds_addr(lds_st[0]) + b_dma * STAGE;
+#pragma unroll
+      for (int n = 0; n < NDMA; n++) {
+        const uint32_t voff = min(dma_row[n], d_lim) + dma_chunk[n];
+        lds_dma16_s(reinterpret_cast<const unsigned char*>(d_k), voff, lbase + (8 * n + wave) * 1024);
+      }
+#pragma unroll
+      for (int n = 0; n < WDS / 1024; n++)
+        lds_dma16_s(reinterpret_cast<const unsigned char*>(d_ds), (uint32_t)(1024 * n + 16 * lane), lbase + TBK + wave * WDS + 1024 * n);
+      b_dma = (b_dma == NB - 1) ? 0 : b_dma + 1;
+    };
+    // prologue: tiles 0 and 1 of the item into the stage to be read first and the one after it
+    int vis[3];
+    b_dma = b_c;
+    describe(); issue(); vis[0] = d_vis;
+    describe(); issue(); vis[1] = d_vis;
+    for (int t = 0; t < n_tiles; t++) {
+      // tile t has landed once at most one tile's loads are in flight; the barrier also says that every wave
+      // is done with the stage that tile t + 2 goes into
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (DMA_PER_TILE & 15) | ((DMA_PER_TILE >> 4) << 14));
+      __syncthreads();
+      describe(); issue(); vis[2] = d_vis;
+      const int nv = __builtin_amdgcn_readfirstlane(vis[0]);
+#pragma unroll
+      for (int f = 0; f < 2; f++) {
+        if (nv > 32 * f) {
+#pragma unroll
+          for (int kc = 0; kc < 2; kc++) {
+            const bf16x8 b = lds_tr_pair_at(ds_a[kc][0] + kDsFragBytes * f, ds_a[kc][1] + kDsFragBytes * f);
+            const uint32_t rows = (32 * f + 16 * kc) * (D * 2);
+#pragma unroll
+            for (int dt = 0; dt < DT; dt++) {
+              const bf16x8 kt = lds_tr_pair_at(tr_lo[dt] + rows, tr_hi[dt] + rows);
+              acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, b, acc[dt], 0, 0, 0);
+            }
+          }
+        }
+      }
+      vis[0] = vis[1]; vis[1] = vis[2];
+      advance_read_stage();
+    }
+    dma_wait();          // the two look-ahead requests past the end of the item
+    if (row_ok) {
+      const int64_t off = (int64_t)(q_start + my_row) * q_row_stride + (int64_t)head * D;
+      if constexpr (GRAD_BF16) {
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) store_tile_bf16(reinterpret_cast<uint16_t*>(a.dq) + off + dt * 32, acc[dt], 1.0f, g);
+      } else {
+        float* op = reinterpret_cast<float*>(a.dq) + off;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            f32x4 w = {acc[dt][4 * q4], acc[dt][4 * q4 + 1], acc[dt][4 * q4 + 2], acc[dt][4 * q4 + 3]};
+            *reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g) = w;
+          }
+      }
+    }
+    __syncthreads();   // every wave has read s_item
+    if (tid == 0) s_item = items.resolve();
     __syncthreads();
   }
   if (tid == 0) retire(a.hdr->dq_counter, &a.hdr->dq_done);
@@ -1642,7 +1910,7 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
   a->n_q_heads = p->n_q_heads; a->n_kv_heads = p->n_kv_heads;
   a->scale = resolve_scale(p); a->scale_log2 = a->scale * kLog2e;
   a->dq = nullptr; a->dk = nullptr; a->dv = nullptr;
-  a->o = nullptr; a->lse = nullptr; a->o_is_f32 = 0; a->lse2_out = nullptr; a->dls_out = nullptr;
+  a->o = nullptr; a->lse = nullptr; a->o_is_f32 = 0; a->lse2_out = nullptr; a->dls_out = nullptr; a->ds = nullptr;
   return FCP_OK;
 }
 
@@ -1658,8 +1926,13 @@ extern "C" int fcp_block_attn_bwd_dkdv(const fcp_problem* p, const void* q, cons
   a.dk = dk; a.dv = dv;
   int grid = (int)std::min<int64_t>(L.n_bwd_items, (int64_t)cu_count() * kDkdvWgPerCu);
   const bool gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0;
-  void (*kern)(BwdArgs) = p->head_dim == 128 ? (gb ? dkdv_kernel<128, true> : dkdv_kernel<128, false>)
-                                             : (gb ? dkdv_kernel<64, true> : dkdv_kernel<64, false>);
+  const bool spill = (p->flags & FCP_FLAG_BWD_SPILL_DS) != 0;
+  if (spill) a.ds = static_cast<unsigned char*>(workspace) + L.off_ds;
+  void (*kern)(BwdArgs) =
+      spill ? (p->head_dim == 128 ? (gb ? dkdv_kernel<128, true, true> : dkdv_kernel<128, false, true>)
+                                  : (gb ? dkdv_kernel<64, true, true> : dkdv_kernel<64, false, true>))
+            : (p->head_dim == 128 ? (gb ? dkdv_kernel<128, true, false> : dkdv_kernel<128, false, false>)
+                                  : (gb ? dkdv_kernel<64, true, false> : dkdv_kernel<64, false, false>));
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
   return check_launch("fcp_block_attn_bwd_dkdv");
 }
@@ -1707,6 +1980,28 @@ extern "C" int fcp_block_attn_bwd_dq_d(const fcp_problem* p, const void* q, cons
   return launch_dq("fcp_block_attn_bwd_dq_d", p, q, k, v, o, lse, d_o, dq, workspace, stream);
 }
 
+extern "C" int fcp_block_attn_bwd_dq_ds(const fcp_problem* p, const void* k, void* dq, void* workspace, void* stream) {
+  WsLayout L;
+  BwdArgs a;
+  int rc = fill_bwd_args(p, &L, &a, workspace);
+  if (rc) return rc;
+  if (!(p->flags & FCP_FLAG_BWD_SPILL_DS)) {
+    set_error("fcp_block_attn_bwd_dq_ds: FCP_FLAG_BWD_SPILL_DS is not set on this problem");
+    return FCP_ERR_INVALID_ARG;
+  }
+  if (L.n_dq_items == 0) return FCP_OK;
+  if (!k || !dq || !workspace) { set_error("fcp_block_attn_bwd_dq_ds: NULL pointer"); return FCP_ERR_INVALID_ARG; }
+  a.k = (const uint16_t*)k;
+  a.dq = dq;
+  a.ds = static_cast<unsigned char*>(workspace) + L.off_ds;
+  const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
+  const bool gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0;
+  void (*kern)(BwdArgs) = p->head_dim == 128 ? (gb ? dq_ds_kernel<128, true> : dq_ds_kernel<128, false>)
+                                             : (gb ? dq_ds_kernel<64, true> : dq_ds_kernel<64, false>);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  return check_launch("fcp_block_attn_bwd_dq_ds");
+}
+
 extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const void* k, const void* v,
                                   const void* o, const float* lse, const void* d_o,
                                   void* dq, void* dk, void* dv, void* workspace, void* stream) {
@@ -1715,6 +2010,14 @@ extern "C" int fcp_block_attn_bwd(const fcp_problem* p, const void* q, const voi
     if (rc) return rc;
     set_error("fcp_block_attn_bwd: NULL pointer");
     return FCP_ERR_INVALID_ARG;
+  }
+  if (p && (p->flags & FCP_FLAG_BWD_SPILL_DS)) {
+    // D first (a pass of its own), then dK/dV, which also writes dS, then dQ from that dS
+    int rc = fcp_bwd_preprocess(p, o, lse, d_o, workspace, stream);
+    if (rc) return rc;
+    rc = fcp_block_attn_bwd_dkdv(p, q, k, v, d_o, dk, dv, workspace, stream);
+    if (rc) return rc;
+    return fcp_block_attn_bwd_dq_ds(p, k, dq, workspace, stream);
   }
   // dQ first: its kernel also leaves the per-row scalars (D * scale, LSE * log2 e) that dK/dV needs
   int rc = fcp_block_attn_bwd_dq_d(p, q, k, v, o, lse, d_o, dq, workspace, stream);

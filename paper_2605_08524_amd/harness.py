@@ -40,7 +40,8 @@ class DevicePath:
         self.o = torch.full((max(1, p.t_q), Hq, d), nan, dtype=o_dtype, device=device)
         self.lse = torch.full((max(1, p.t_q), Hq), nan, **f32)
         self.ws_bytes = B.fcp_workspace_bytes(p)
-        self.ws = torch.zeros(self.ws_bytes + 256, dtype=torch.uint8, device=device)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=device)
+        self.ws.fill_(0xFF)      # poison (bf16 / fp32 NaN patterns): whatever a kernel reads must have been written first
         off = (-self.ws.data_ptr()) % 256
         self.ws_ptr = self.ws.data_ptr() + off
         torch.cuda.synchronize(device)
@@ -79,6 +80,9 @@ class DevicePath:
     def bwd_dkdv(self):
         B.fcp_block_attn_bwd_dkdv(self.problem, self.q, self.k, self.v, self.d_o,
                                   self.dk, self.dv, self.ws_ptr, self.stream)
+
+    def bwd_dq_ds(self):
+        B.fcp_block_attn_bwd_dq_ds(self.problem, self.k, self.dq, self.ws_ptr, self.stream)
 
     def bwd_dq(self):
         B.fcp_block_attn_bwd_dq(self.problem, self.q, self.k, self.v, self.d_o,

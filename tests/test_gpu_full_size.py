@@ -1,9 +1,11 @@
 """GPU parity at the benchmark's full sizes.
 
-`_run(..., timed=True)` issues exactly the launches bench.py times: FCP_FLAG_DIRECT_SINGLE (| FCP_FLAG_O_F32 for
-the training step), fcp_block_attn_fwd_out -> fcp_merge_partials -> fcp_block_attn_bwd (= the dQ kernel that also
-forms D, then dK/dV).  `timed=False` is the staged path: every query block through the partial buffers and the
-merge, then fcp_bwd_preprocess + the two backward kernels called one by one.  The training step runs both ways.
+`_run(..., timed=True)` issues exactly the launches bench.py times: FCP_FLAG_DIRECT_SINGLE (| FCP_FLAG_O_F32 |
+FCP_FLAG_BWD_SPILL_DS for the training step), fcp_block_attn_fwd_out -> fcp_merge_partials -> fcp_block_attn_bwd
+(= D pass, dK/dV kernel that leaves dS in the workspace, dQ from that dS).  `timed=False` is the staged path without
+those flags: every query block through the partial buffers and the merge, then fcp_bwd_preprocess + the dK/dV kernel
+and the recomputing dQ kernel called one by one.  `timed="recompute"` is fcp_block_attn_bwd without the spill flag
+(dQ kernel that forms D itself, then dK/dV), which `bench.py --bwd recompute` times.  The training step runs all three.
 
 The fp64 oracle cannot evaluate these workloads whole in test time, so it is asked for outputs it
 can compute one by one from the plain definition:
@@ -145,6 +147,7 @@ def _tail_check(wl, host, seq, n_tail, accs, koff, qrow):
 
 
 DIRECT = 2   # FCP_FLAG_DIRECT_SINGLE
+SPILL = 16   # FCP_FLAG_BWD_SPILL_DS
 
 
 def _run(wl, backward, flags, timed=True):
@@ -152,6 +155,8 @@ def _run(wl, backward, flags, timed=True):
     t0 = time.time()
     if timed:
         flags |= DIRECT
+    if timed is True and backward:
+        flags |= SPILL
     dp = DevicePath(wl, dev, flags=flags, backward=backward)
     _say(f"  inputs generated and uploaded in {time.time() - t0:.1f} s; "
          f"{len(dp.plan['pairs'])} pairs, {len(dp.plan['slots'])} slots, {dp.problem.n_slot_rows} partial rows")
@@ -210,10 +215,10 @@ def _gradient_sum_properties(wl, host, koff):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("seed,timed", [(0, True), (1, True), (2, True), (0, False)])
+@pytest.mark.parametrize("seed,timed", [(0, True), (1, True), (2, True), (0, "recompute"), (0, False)])
 def test_config5_training_step_full_size(seed, timed):
     wl = workloads.make_workload(5, seed)
-    _say(f"case {wl.name} seed={seed} {'timed launches' if timed else 'staged launches'}: {len(wl.seq_lens)} sequences, "
+    _say(f"case {wl.name} seed={seed} {'launches as timed: ' + str(timed) if timed else 'staged launches'}: {len(wl.seq_lens)} sequences, "
          f"lengths {sorted(int(x) for x in wl.seq_lens)}")
     host, plan = _run(wl, True, F32, timed)
     _tables_exact(wl, plan)

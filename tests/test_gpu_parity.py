@@ -218,8 +218,11 @@ def test_all_logits_strongly_negative_with_ragged_blocks(causal):
     _say(f"  lse: max relative error {err:.3e}")
     assert err <= TOL_LSE
     dq, dk, dv = orc.worker_bwd(q, k, v, wl.d_o(), wl.seq_lens, wl.block_size, wl.causal, None, 1.0)
+    # dQ_i = sum_j dS_ij k_j with every k_j close to -2u (norm 16) and sum_j dS_ij = 0: the large common part
+    # cancels exactly in exact arithmetic, so what is left of it after dS is rounded to bf16 is an error 16 times
+    # the usual one next to a result made of the small differences.  The relative bar for dQ is widened for that.
     for name, ref in (("dq", dq), ("dk", dk), ("dv", dv)):
-        _check(name, res[name], ref, tol_abs=TOL_ABS * 8.0, tol_rel=TOL_REL)
+        _check(name, res[name], ref, tol_abs=TOL_ABS * 8.0, tol_rel=0.1 if name == "dq" else TOL_REL)
 
 
 @pytest.mark.parametrize("f32", [0, 1])
@@ -248,6 +251,58 @@ def test_backward_stage_entry_points_agree(f32):
         err = float(np.max(np.abs(x - y)))
         _say(f"  {nm}: fused vs staged max-abs {err:.3e}")
         assert err <= 2e-3
+
+
+SPILL = 16   # FCP_FLAG_BWD_SPILL_DS
+
+
+@pytest.mark.parametrize("case", range(len(EDGE)))
+def test_edge_cases_bwd_with_spilled_ds(case):
+    """The backward that keeps dS in the workspace (dK/dV kernel writes it, dQ is one streaming contraction over
+    it): same bars against the oracle as the recomputing backward, on every edge case."""
+    lens, bs, causal, c, hq, hkv, d, owned = EDGE[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=100 + case, name=f"edge{case}-spill")
+    _full_parity(wl, backward=True, flags=F32 | SPILL, partials=False)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config1_tiny_with_spilled_ds(seed):
+    wl = workloads.make_workload(1, seed)
+    _full_parity(wl, backward=True, flags=F32 | SPILL | DIRECT, partials=False)
+
+
+def test_spilled_ds_backward_stage_calls_and_bf16_gradients():
+    """fcp_block_attn_bwd with the spill flag = preprocess, dK/dV, dQ-from-dS called one by one (bit-equal);
+    dK / dV are the recomputing backward's bit for bit (the producer forms the same P and dS); dQ agrees with
+    the recomputing kernel to rounding; bf16 gradients are the fp32 ones rounded once."""
+    from paper_2605_08524_amd.harness import DevicePath
+    dev = torch.device("cuda:0")
+    wl = workloads.custom_workload([900, 50, 1300, 333], 256, 1, 2, 8, 2, 128, seed=62, name="spill-stages")
+    _say(f"case {wl.name}")
+    res = {}
+    for name, flags in (("recompute", F32), ("spill", F32 | SPILL), ("spill-bf16", F32 | SPILL | 8)):
+        dp = DevicePath(wl, dev, flags=flags, backward=True)
+        dp.fwd(); dp.merge(); dp.bwd()
+        torch.cuda.synchronize(dev)
+        res[name] = [t.float().cpu().numpy().copy() for t in (dp.dq, dp.dk, dp.dv)]
+        if name == "spill":
+            for t in (dp.dq, dp.dk, dp.dv):
+                t.fill_(float("nan"))
+            dp.bwd_pre(); dp.bwd_dkdv(); dp.bwd_dq_ds()
+            torch.cuda.synchronize(dev)
+            for x, t in zip(res[name], (dp.dq, dp.dk, dp.dv)):
+                assert np.array_equal(x, t.cpu().numpy())
+        del dp
+    for x in res.values():
+        assert all(np.isfinite(t).all() for t in x)
+    # D comes from the preprocess pass here and from the dQ kernel there: same values up to summation order
+    for nm, x, y in zip(("dq", "dk", "dv"), res["recompute"], res["spill"]):
+        err = float(np.max(np.abs(x - y)))
+        _say(f"  {nm}: spill vs recompute max-abs {err:.3e}")
+        assert err <= (6e-3 if nm == "dq" else 2e-3)
+    for x, y in zip(res["spill"], res["spill-bf16"]):
+        want = torch.from_numpy(x).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(want, y)
 
 
 PART_BF16 = 4   # FCP_FLAG_PART_BF16
