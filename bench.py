@@ -26,14 +26,27 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a
-# plain copy of known size in the same runs (profiles/cfg5_training_step_hbm_traffic.txt); None
-# for a workload or kernel that has not been measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg5-training-step-fwd-bwd", "fwd_kernel"): 2.781e9,
-    ("cfg5-training-step-fwd-bwd", "dkdv_kernel"): 5.255e9,
-    ("cfg5-training-step-fwd-bwd", "dq_kernel"): 4.430e9,
-}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "cfg5_training_step_hbm_traffic.txt")
+
+
+def measured_traffic(workload, kernel_instance):
+    """HBM bytes per launch of `kernel_instance` (its full name, template arguments included) as recorded in the
+    tracked rocprofv3 summary of the training step (FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a plain copy
+    of known size in the same runs).  None unless that file is about this workload and lists exactly this kernel
+    instance: a figure carried over from a profile must not outlive the kernel it was measured on."""
+    try:
+        lines = open(TRAFFIC_PROFILE).read().splitlines()
+    except OSError:
+        return None
+    if not any(l.startswith("workload: ") and l.split()[1] == workload for l in lines):
+        return None
+    for l in lines:
+        if l.startswith(kernel_instance + " "):
+            try:
+                return float(l.split()[-1]) * 1e9       # last column: total GB
+            except ValueError:
+                return None
+    return None
 
 
 def pair_flops(plan, n_q_heads, head_dim):
@@ -89,19 +102,23 @@ def sweep(args):
     and saturates above 4K; its system picks 4K blocks, coalesce degree 16) redone for this path,
     where one persistent launch covers all slots.  One JSON line per point."""
     import torch
-    from paper_2605_08524_amd import FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, workloads
+    from paper_2605_08524_amd import FCP_FLAG_BWD_SPILL_DS, FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, workloads
     from paper_2605_08524_amd.harness import DevicePath
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream(dev)
     wl = workloads.make_workload(5, args.seed)
+    spill = args.bwd == "spill"
     for bs in (256, 512, 1024, 2048, 4096, 8192):
         for c in (1, 4, 16, 0):
             wl.block_size, wl.coalesce = bs, c
-            dp = DevicePath(wl, dev, flags=FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_O_F32, backward=True, stream=stream)
+            dp = DevicePath(wl, dev, flags=FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_O_F32 | (FCP_FLAG_BWD_SPILL_DS if spill else 0),
+                            backward=True, stream=stream)
             f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
-            stages = [dp.fwd, dp.merge, dp.bwd_dq_d, dp.bwd_dkdv]
+            # four timed stages either way: forward, merge, then (D pass + dK/dV, dQ from dS) or (dQ with D, dK/dV)
+            stages = [dp.fwd, dp.merge, (lambda: (dp.bwd_pre(), dp.bwd_dkdv())), dp.bwd_dq_ds] if spill else \
+                     [dp.fwd, dp.merge, dp.bwd_dq_d, dp.bwd_dkdv]
             for _ in range(args.warmup):
                 for fn in stages:
                     fn()
@@ -117,7 +134,9 @@ def sweep(args):
             step_ms = sum(ms)
             print(json.dumps({
                 "block_size": bs, "coalesce": c, "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
-                "nnz_per_head": nnz, "ms": {k: round(v, 3) for k, v in zip(("fwd", "merge", "bwd_dq", "bwd_dkdv"), ms)},
+                "backward": args.bwd,
+                "nnz_per_head": nnz, "ms": {k: round(v, 3) for k, v in zip(("fwd", "merge", "bwd_pre+dkdv", "bwd_dq_ds") if spill else
+                                                                           ("fwd", "merge", "bwd_dq", "bwd_dkdv"), ms)},
                 "ms_per_step": round(step_ms, 3), "tflops": round((f_fwd + f_bwd) / step_ms / 1e9, 1),
                 "fwd_tflops": round(f_fwd / (ms[0] + ms[1]) / 1e9, 1)}), flush=True)
             del dp
@@ -209,6 +228,250 @@ def distribute(args):
                       "ms_per_step": round(ms, 3), "tflops": round((f_fwd + f_bwd) / ms / 1e9, 1)}), flush=True)
 
 
+def merge_record(wl, dev, stream, steps, out_f32):
+    """The merge where it is HBM-bound: the same batch at coalesce degree 1, so that every query block has one partial
+    per KV block (3.5 GB of fp32 partials for the training batch, far beyond the 256 MB cache).  The forward fills the
+    partials once; the merge alone is timed with events on the launch stream."""
+    import numpy as np
+    import torch
+    from paper_2605_08524_amd import FCP_FLAG_O_F32
+    from paper_2605_08524_amd.harness import DevicePath
+    c_before = wl.coalesce
+    wl.coalesce = 1
+    try:
+        dp = DevicePath(wl, dev, flags=FCP_FLAG_O_F32 if out_f32 else 0, backward=False, stream=stream)
+    finally:
+        wl.coalesce = c_before
+    dp.fwd()
+    dp.merge()
+    torch.cuda.synchronize(dev)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record(stream)
+        dp.merge()
+        e1.record(stream)
+    torch.cuda.synchronize(dev)
+    ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+    slots, qb = dp.plan["slots"], dp.plan["q_blocks"]
+    cnt = np.bincount(slots[:, 0], minlength=len(qb))
+    part_rows = int((cnt * qb[:, 3]).sum())
+    rows = int(qb[:, 3].sum())
+    nbytes = part_rows * wl.n_q_heads * (wl.head_dim * 4 + 4) + rows * wl.n_q_heads * (wl.head_dim * (4 if out_f32 else 2) + 4)
+    rec = {"workload": f"{wl.name} at coalesce degree 1 ({len(slots)} partial slots)", "kernel": f"fcp::merge_kernel<{wl.head_dim}>",
+           "algorithmic_bytes": nbytes, "ms": round(ms, 4), "achieved": round(nbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "bound": "hbm", "frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+           "traffic": measured_traffic(CONFIG5_NAME, f"fcp::merge_kernel<{wl.head_dim}>")}
+    del dp
+    torch.cuda.empty_cache()
+    return rec
+
+
+CONFIG5_NAME = "cfg5-training-step-fwd-bwd"
+
+
+class PowerSampler:
+    """Board power and shader clock from the driver's sysfs files (hwmon power1_input / power1_average in microwatts,
+    pp_dpm_sclk's current level), sampled on a thread while a kernel runs in a loop."""
+
+    def __init__(self):
+        import glob
+        self.power = self.sclk = self.cap = None
+        for card in sorted(glob.glob("/sys/class/drm/card*/device")):
+            hw = glob.glob(card + "/hwmon/hwmon*")
+            for h in hw:
+                for name in ("power1_input", "power1_average"):
+                    if self.power is None and os.path.exists(os.path.join(h, name)):
+                        self.power = os.path.join(h, name)
+                if self.cap is None and os.path.exists(os.path.join(h, "power1_cap")):
+                    self.cap = os.path.join(h, "power1_cap")
+            if self.power and os.path.exists(os.path.join(card, "pp_dpm_sclk")):
+                self.sclk = os.path.join(card, "pp_dpm_sclk")
+                break
+        self.rows, self.label, self.stop = [], None, False
+
+    @staticmethod
+    def _read(path):
+        try:
+            return open(path).read()
+        except OSError:
+            return ""
+
+    def _loop(self):
+        import re
+        while not self.stop:
+            if self.label is not None:
+                try:
+                    w = float(self._read(self.power)) / 1e6
+                except ValueError:
+                    w = float("nan")
+                mhz = float("nan")
+                for line in self._read(self.sclk).splitlines():
+                    if line.rstrip().endswith("*"):
+                        m = re.search(r"(\d+)\s*[Mm]hz", line)
+                        if m:
+                            mhz = float(m.group(1))
+                self.rows.append((self.label, w, mhz))
+            time.sleep(0.02)
+
+    def start(self):
+        import threading
+        self.thread = threading.Thread(target=self._loop, daemon=True)
+        self.thread.start()
+
+    def mean(self, label):
+        rows = [r for r in self.rows if r[0] == label]
+        rows = rows[len(rows) // 3:]            # the clock needs a moment to settle on a new kind of load
+        if not rows:
+            return None, None
+        return sum(r[1] for r in rows) / len(rows), sum(r[2] for r in rows) / len(rows)
+
+
+def power_study(args):
+    """Board power and shader clock while each kernel of the training step runs alone in a loop (about 2.5 s each), on
+    the workload's N(0,1) operands and on all-zero operands, next to a pure MFMA stream and plain memory streams.
+    Shows which kernels run into the board's power limit (the clock then pays for every joule the kernel spends).
+    One JSON line per case."""
+    import torch
+    from paper_2605_08524_amd import (FCP_FLAG_BWD_SPILL_DS, FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, fcp_device_info, fcp_mfma_probe,
+                                      workloads)
+    from paper_2605_08524_amd.harness import DevicePath
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream(dev)
+    ps = PowerSampler()
+    if not ps.power or not ps.sclk:
+        print(json.dumps({"error": "no hwmon power / pp_dpm_sclk files visible on this box"}))
+        return
+    wl = workloads.make_workload(5, args.seed)
+    dp = DevicePath(wl, dev, flags=FCP_FLAG_DIRECT_SINGLE | FCP_FLAG_O_F32 | FCP_FLAG_BWD_SPILL_DS, backward=True, stream=stream)
+    n_cu = fcp_device_info()["n_compute_units"]
+    out = torch.zeros(8 * n_cu, dtype=torch.float32, device=dev)
+    for fn in (dp.fwd, dp.merge, dp.bwd_pre, dp.bwd_dq_d, dp.bwd_dkdv, dp.bwd_dq_ds):
+        fn()
+    torch.cuda.synchronize(dev)
+    f_fwd, f_bwd, nnz = pair_flops(dp.plan, wl.n_q_heads, wl.head_dim)
+    unit = wl.head_dim * wl.n_q_heads * nnz
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    ps.start()
+    time.sleep(1.5)
+    cap_w = float(ps._read(ps.cap) or "nan") / 1e6 if ps.cap else None
+
+    def run(label, fn, flops=None, nbytes=None, secs=2.5):
+        time.sleep(0.8)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ps.label = label
+        t0, n = time.time(), 0
+        e0.record(stream)
+        while time.time() - t0 < secs:
+            for _ in range(10):
+                fn()
+            n += 10
+            torch.cuda.synchronize(dev)
+        e1.record(stream)
+        torch.cuda.synchronize(dev)
+        ps.label = None
+        ms = e0.elapsed_time(e1) / n
+        w, mhz = ps.mean(label)
+        line = {"case": label, "ms_per_launch": round(ms, 4), "board_w": round(w, 1), "sclk_mhz": round(mhz), "power_cap_w": cap_w}
+        if flops:
+            line["executed_tflops"] = round(flops / ms / 1e9, 1)
+            line["pj_per_executed_flop_above_idle"] = round((w - idle_w) * ms * 1e-3 / flops * 1e12, 3)
+        if nbytes:
+            line["gb_per_s"] = round(nbytes / ms / 1e6, 1)
+            line["pj_per_byte_above_idle"] = round((w - idle_w) * ms * 1e-3 / nbytes * 1e12, 1)
+        print(json.dumps(line), flush=True)
+
+    ps.label = "idle"
+    time.sleep(1.5)
+    ps.label = None
+    idle_w, idle_mhz = ps.mean("idle")
+    print(json.dumps({"case": "idle", "board_w": round(idle_w, 1), "sclk_mhz": round(idle_mhz), "power_cap_w": cap_w}), flush=True)
+    probe_flops = n_cu * 8 * 6000 * 16 * 32768.0
+    run("mfma stream, zero operands", lambda: fcp_mfma_probe(0, 6000, out, stream), flops=probe_flops)
+    run("mfma stream, random operands", lambda: fcp_mfma_probe(2, 6000, out, stream), flops=probe_flops)
+    cases = [("fwd_kernel", dp.fwd, 4 * unit), ("dkdv_kernel, dS spilled", dp.bwd_dkdv, 8 * unit), ("dq_ds_kernel", dp.bwd_dq_ds, 2 * unit),
+             ("dq_kernel (recomputing, with D)", dp.bwd_dq_d, 6 * unit)]
+    for name, fn, fl in cases:
+        run(name + ", N(0,1) operands", fn, flops=fl)
+    run("delta_kernel", dp.bwd_pre, nbytes=wl.t_q * wl.n_q_heads * (wl.head_dim * 6 + 12))
+    run("device copy 1 GiB (read + write)", lambda: dst.copy_(src), nbytes=2 * src.numel() * 4)
+    run("device fill 1 GiB (write)", lambda: dst.fill_(1.5), nbytes=src.numel() * 4)
+    for t in (dp.q, dp.k, dp.v, dp.d_o):
+        t.fill_(0.0)
+    torch.cuda.synchronize(dev)
+    for name, fn, fl in cases:
+        run(name + ", zero operands", fn, flops=fl)
+    ps.stop = True
+
+
+def probes(args):
+    """Chip rates behind the kernels' design (include/fcp_probe.h): the matrix pipe with vector work beside it, LDS
+    throughput per access pattern, fp32 atomic adds to memory.  One JSON line per case; rates per compute unit are
+    given per nanosecond and, for reading against the LDS width, per cycle of the shader clock sampled during the case."""
+    import torch
+    from paper_2605_08524_amd import fcp_atomic_probe, fcp_device_info, fcp_lds_probe, fcp_mfma_valu_probe
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream(dev)
+    n_cu = fcp_device_info()["n_compute_units"]
+    ps = PowerSampler()
+    sampling = bool(ps.power and ps.sclk)
+    if sampling:
+        ps.start()
+
+    def timed(label, fn, min_s=1.0):
+        fn()
+        torch.cuda.synchronize(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ps.label = label
+        t0, n = time.time(), 0
+        e0.record(stream)
+        while time.time() - t0 < min_s:
+            fn()
+            n += 1
+            torch.cuda.synchronize(dev)
+        e1.record(stream)
+        torch.cuda.synchronize(dev)
+        ps.label = None
+        w, mhz = ps.mean(label) if sampling else (None, None)
+        return e0.elapsed_time(e1) / n, w, mhz
+
+    out = torch.zeros(8 * n_cu, dtype=torch.float32, device=dev)
+    for kind, kname in ((0, "zero"), (2, "random")):
+        base = None
+        for valu in (0, 2, 4, 6, 8, 12):
+            iters = 20000
+            ms, w, mhz = timed(f"mfma+{valu} {kname}", lambda: fcp_mfma_valu_probe(kind, valu, iters, out, stream))
+            tf = n_cu * 8 * iters * 16 * 32768.0 / ms / 1e9
+            base = base or tf
+            print(json.dumps({"probe": "mfma stream with vector work", "operands": kname, "fp32_fma_per_mfma": valu, "ms": round(ms, 3),
+                              "mfma_tflops": round(tf, 1), "relative_to_no_vector_work": round(tf / base, 3),
+                              "board_w": w and round(w), "sclk_mhz": mhz and round(mhz)}), flush=True)
+    src = torch.zeros(65536, dtype=torch.uint8, device=dev)
+    names = {0: ("ds_read_b128, swizzled rows", 1024), 1: ("ds_read_b64_tr_b16", 512), 2: ("ds_write_b128", 1024), 3: ("ds_write_b64", 512),
+             4: ("LDS-DMA global_load_lds_dwordx4 (source in L2)", 1024)}
+    for mode, (name, nbytes) in names.items():
+        for waves in (4, 8):
+            iters = 20000
+            ms, w, mhz = timed(f"lds {mode} {waves}", lambda: fcp_lds_probe(mode, waves, iters, src, out, stream))
+            per_cu = waves * iters * 16.0 * nbytes
+            line = {"probe": "lds throughput per compute unit", "access": name, "waves": waves, "ms": round(ms, 3),
+                    "bytes_per_ns": round(per_cu / ms / 1e6, 1), "sclk_mhz": mhz and round(mhz)}
+            if mhz:
+                line["bytes_per_clk"] = round(per_cu / ms / 1e6 / (mhz / 1e3), 1)
+            print(json.dumps(line), flush=True)
+    n_rows, stride = 65536, 4096                 # 1 GiB of fp32: rows of 32 heads x 128
+    buf = torch.zeros(n_rows * stride, dtype=torch.float32, device=dev)
+    for wg in (1, 2, 4):
+        iters = 2000
+        ms, w, mhz = timed(f"atomic {wg}", lambda: fcp_atomic_probe(buf, n_rows, stride, iters, wg, stream), min_s=0.5)
+        payload = n_cu * wg * 256 * iters * 16 * 4.0
+        print(json.dumps({"probe": "fp32 atomic add to memory (dQ accumulation pattern)", "workgroups_per_cu": wg, "ms": round(ms, 3),
+                          "payload_tb_per_s": round(payload / ms / 1e9, 3), "atomics_per_ns": round(payload / 4 / ms / 1e6, 1)}), flush=True)
+    ps.stop = True
+
+
 def mfma_sustained(dev, stream):
     """What the matrix pipes sustain on a pure stream of the kernels' MFMA, by operand values
     (fcp_mfma_probe): the chip lowers its clock under the power drawn by random operands, so the
@@ -256,6 +519,14 @@ def main():
                          "its FETCH_SIZE / WRITE_SIZE give the scale factor for the kernels' HBM traffic")
     ap.add_argument("--sweep", action="store_true",
                     help="block size x coalesce degree sweep of the training step (one JSON line per point) instead of the benchmark line")
+    ap.add_argument("--power", action="store_true",
+                    help="board power and shader clock per kernel (sysfs sampling while each kernel loops), one JSON line per case, "
+                         "instead of the benchmark line")
+    ap.add_argument("--probes", action="store_true",
+                    help="chip rates behind the kernels' design (MFMA with vector work beside it, LDS throughput per access "
+                         "pattern, fp32 atomics), one JSON line per case, instead of the benchmark line")
+    ap.add_argument("--no-merge-record", action="store_true",
+                    help="skip the separate measurement of the merge kernel on the batch at coalesce degree 1")
     ap.add_argument("--distribute", action="store_true",
                     help="block distributor + congestion-free solver study on synthetic length traces (host timings, "
                          "imbalance ratios; the most loaded worker's share on the GPU if there is one) instead of the benchmark line")
@@ -269,6 +540,12 @@ def main():
         return
     if args.distribute:
         distribute(args)
+        return
+    if args.power:
+        power_study(args)
+        return
+    if args.probes:
+        probes(args)
         return
     import torch
     from paper_2605_08524_amd import (FCP_FLAG_BWD_SPILL_DS, FCP_FLAG_DIRECT_SINGLE, FCP_FLAG_O_F32, FCP_FLAG_PART_BF16,
@@ -344,6 +621,9 @@ def main():
     unit = wl.head_dim * wl.n_q_heads * nnz
     kernel_flops = {"fwd": 4 * unit, "bwd_dkdv": 8 * unit, "bwd_dq": (2 if spill else 6) * unit}
     kernel_name = {"fwd": "fwd_kernel", "bwd_dkdv": "dkdv_kernel", "bwd_dq": "dq_ds_kernel" if spill else "dq_kernel"}
+    tf = "true" if spill else "false"
+    kernel_instance = {"fwd": f"fcp::fwd_kernel<{wl.head_dim}>", "bwd_dkdv": f"fcp::dkdv_kernel<{wl.head_dim}, false, {tf}>",
+                       "bwd_dq": f"fcp::dq_ds_kernel<{wl.head_dim}, false>" if spill else f"fcp::dq_kernel<{wl.head_dim}, true, false>"}
     cands = [k for k in kernel_flops if k in stage_ms]
     dom = max(cands, key=lambda k: stage_ms[k])
     achieved = kernel_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
@@ -383,12 +663,18 @@ def main():
             "kernel": kernel_name[dom],
             "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name[dom])),
+            "kernel_instance": kernel_instance[dom],
+            "traffic": measured_traffic(wl.name, kernel_instance[dom]),
+            "traffic_source": os.path.relpath(TRAFFIC_PROFILE, ROOT) + " (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command; null if that file "
+                              "does not list this kernel instance on this workload)",
             "avg_launch_ms": round(stage_ms[dom], 4),
         },
         "grid": info, "setup_s": round(setup_s, 2),
         "host_ms": {"plan_blocks": round(dp.plan_ms, 3), "queue_build": round(dp.queue_build_ms, 3)},
     }
+    if args.config == 5 and not args.no_merge_record and not args.heads and args.inputs == "normal":
+        # the merge launches nothing in the training configuration (one slot per query block): measured on its own
+        out["merge"] = merge_record(wl, dev, stream, max(5, args.steps), out_f32=True)
     if not args.no_mfma_probe:
         # context for the roofline, measured after the timed region: the published peak stays the denominator of "frac"
         sus = mfma_sustained(dev, stream)

@@ -34,6 +34,37 @@ extern "C" {
  */
 int fcp_mfma_probe(int32_t operand_kind, int32_t iters, float* out, void* stream);
 
+/*
+ * fcp_mfma_valu_probe -- fcp_mfma_probe with vector-ALU work beside the MFMAs: after every MFMA the wave issues
+ * valu_per_mfma (0, 2, 4, 6, 8 or 12) independent fp32 FMAs.  Shows what the vector work that an attention kernel
+ * has to place between its MFMAs (exponentials, masks, packing) costs the matrix pipe: a SIMD issues one
+ * instruction per wave every few cycles, and both kinds share those slots.  FLOPs counted = the MFMAs only.
+ */
+int fcp_mfma_valu_probe(int32_t operand_kind, int32_t valu_per_mfma, int32_t iters, float* out, void* stream);
+
+/*
+ * fcp_lds_probe -- raw LDS throughput of a compute unit for the access patterns of the attention kernels.
+ * One workgroup of n_waves (4 or 8) waves per compute unit; every wave issues iters x 16 instructions of one kind:
+ *   mode 0: ds_read_b128, 1 KB per instruction (row operands of a swizzled tile)
+ *   mode 1: ds_read_b64_tr_b16, 512 B per instruction (transposed operands)
+ *   mode 2: ds_write_b128, 1 KB     mode 3: ds_write_b64, 512 B
+ *   mode 4: LDS-DMA (global_load_lds_dwordx4), 1 KB per instruction, from `src`, a 64 KB device buffer that stays in
+ *           the L2 cache: what a tile load costs on the LDS side.
+ * Bytes per compute unit = n_waves x iters x 16 x (bytes per instruction); the caller times the launch.
+ * src: device, 64 KB (read in mode 4 only, but required); out: device, one float (contents meaningless).
+ */
+int fcp_lds_probe(int32_t mode, int32_t n_waves, int32_t iters, const void* src, float* out, void* stream);
+
+/*
+ * fcp_atomic_probe -- fp32 atomic adds to memory in the pattern with which a KV-stationary backward would
+ * accumulate dQ (per wave and iteration 16 rows of 32 consecutive floats, rows row_stride floats apart): the
+ * measurement behind the choice of a backward without atomics.
+ * workgroups_per_cu (1..8) workgroups of 4 waves per compute unit, iters iterations each; payload bytes =
+ * n_compute_units x workgroups_per_cu x 256 x iters x 16 x 4.  buf: device, n_rows x row_stride floats
+ * (n_rows >= 2048, row_stride >= 256), accumulated into.
+ */
+int fcp_atomic_probe(float* buf, int64_t n_rows, int32_t row_stride, int32_t iters, int32_t workgroups_per_cu, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,7 +13,7 @@ _BINDING_NAMES = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_block_attn_fwd_static",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv",
-    "fcp_block_attn_bwd_dq", "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_device_info", "fcp_last_error", "fcp_mfma_probe",
+    "fcp_block_attn_bwd_dq", "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_device_info", "fcp_last_error", "fcp_mfma_probe", "fcp_mfma_valu_probe", "fcp_lds_probe", "fcp_atomic_probe",
     "fcp_assign_blocks", "fcp_block_costs", "fcp_coalesce_stages", "fcp_comm_edges", "fcp_pack_units",
     "fcp_solve_matchings", "fcp_worker_blocks",
 )

@@ -34,7 +34,7 @@ EXPORTS = (
     "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_block_attn_fwd_static",
-    "fcp_last_error", "fcp_device_info", "fcp_mfma_probe",
+    "fcp_last_error", "fcp_device_info", "fcp_mfma_probe", "fcp_mfma_valu_probe", "fcp_lds_probe", "fcp_atomic_probe",
     "fcp_block_costs", "fcp_assign_blocks", "fcp_worker_blocks", "fcp_comm_edges", "fcp_solve_matchings",
     "fcp_coalesce_stages", "fcp_pack_units",
 )
@@ -96,6 +96,9 @@ def _load():
     lib.fcp_last_error.restype = C.c_char_p
     lib.fcp_device_info.argtypes = [i32p, i32p, i32p]
     lib.fcp_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.fcp_mfma_valu_probe.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.fcp_lds_probe.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fcp_atomic_probe.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     for name in EXPORTS:
         if name != "fcp_last_error":
             getattr(lib, name).restype = C.c_int
@@ -246,6 +249,18 @@ def fcp_device_info():
 def fcp_mfma_probe(operand_kind: int, iters: int, out, stream=None):
     """Launches the pure-MFMA measurement kernel; the caller times it.  FLOPs = CUs * 8 * iters * 16 * 32768."""
     _check(_lib.fcp_mfma_probe(int(operand_kind), int(iters), _ptr(out), _stream(stream)))
+
+
+def fcp_mfma_valu_probe(operand_kind: int, valu_per_mfma: int, iters: int, out, stream=None):
+    _check(_lib.fcp_mfma_valu_probe(int(operand_kind), int(valu_per_mfma), int(iters), _ptr(out), _stream(stream)))
+
+
+def fcp_lds_probe(mode: int, n_waves: int, iters: int, src, out, stream=None):
+    _check(_lib.fcp_lds_probe(int(mode), int(n_waves), int(iters), _ptr(src), _ptr(out), _stream(stream)))
+
+
+def fcp_atomic_probe(buf, n_rows: int, row_stride: int, iters: int, workgroups_per_cu: int, stream=None):
+    _check(_lib.fcp_atomic_probe(_ptr(buf), int(n_rows), int(row_stride), int(iters), int(workgroups_per_cu), _stream(stream)))
 
 
 # ---------------------------------------------------------------- host-side scheduling (fcp_sched.h)

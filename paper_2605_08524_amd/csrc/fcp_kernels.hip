@@ -22,7 +22,6 @@
 #include <vector>
 
 #include "fcp_internal.h"
-#include "fcp_probe.h"
 
 namespace fcp {
 
@@ -1659,56 +1658,6 @@ __global__ void __launch_bounds__(512, 2) dq_ds_kernel(BwdArgs a) {
 }
 
 // =====================================================================================
-// Measurement aid: a pure MFMA stream on register operands of chosen values (see fcp_mfma_probe).
-// =====================================================================================
-__global__ void __launch_bounds__(512, 2) mfma_probe_kernel(int kind, int iters, float* out) {
-  u32x4 fa[8], fb[8];
-#pragma unroll
-  for (int i = 0; i < 16; i++) {
-    u32x4 f = {0, 0, 0, 0};
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-      float v[2] = {0.f, 0.f};
-#pragma unroll
-      for (int half = 0; half < 2; half++) {
-        if (kind == 1) v[half] = 0.5f;
-        if (kind == 2) {
-          // integer hash of (thread, fragment, element), then the sum of its four bytes: close to normal
-          uint32_t h = ((threadIdx.x * 16u + i) * 8u + 2u * e + half) * 2654435761u;
-          h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
-          v[half] = ((float)((h & 255u) + ((h >> 8) & 255u) + ((h >> 16) & 255u) + (h >> 24)) - 510.f) * (1.f / 147.8f);
-        }
-      }
-      f[e] = pack_bf16(v[0], v[1]);
-    }
-    if (i < 8) fa[i] = f; else fb[i - 8] = f;
-  }
-  f32x16 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; j++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) acc[j][r] = 0.f;
-  for (int it = 0; it < iters; it++) {
-#pragma unroll
-    for (int m = 0; m < 16; m++)
-      acc[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[m & 7]), as_bf16x8(fb[(m * 3) & 7]), acc[m & 3], 0, 0, 0);
-    if ((it & 63) == 63) {      // random operands make the sums a random walk: keep them bounded
-#pragma unroll
-      for (int j = 0; j < 4; j++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[j][r] *= 0.125f;
-    }
-  }
-  float s = 0.f;
-#pragma unroll
-  for (int j = 0; j < 4; j++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) s += acc[j][r];
-  s += xor32(s);
-  if ((threadIdx.x & 63) == 0) out[blockIdx.x * 8 + (threadIdx.x >> 6)] = s;
-}
-
-// =====================================================================================
 // Launchers
 // =====================================================================================
 static int cu_count() {
@@ -1747,15 +1696,6 @@ extern "C" int fcp_device_info(int32_t* n_compute_units, int32_t* fwd_grid, int3
   if (fwd_grid) *fwd_grid = n * kFwdWgPerCu;
   if (bwd_grid) *bwd_grid = n * kDkdvWgPerCu;
   return FCP_OK;
-}
-
-extern "C" int fcp_mfma_probe(int32_t operand_kind, int32_t iters, float* out, void* stream) {
-  if (!out || iters <= 0 || operand_kind < 0 || operand_kind > 2) {
-    set_error("fcp_mfma_probe: out must be non-NULL, iters > 0, operand_kind in 0..2");
-    return FCP_ERR_INVALID_ARG;
-  }
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(cu_count()), dim3(512), 0, (hipStream_t)stream, (int)operand_kind, (int)iters, out);
-  return check_launch("fcp_mfma_probe");
 }
 
 static int launch_fwd(const char* who, const fcp_problem* p, const void* q, const void* k, const void* v,

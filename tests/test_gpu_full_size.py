@@ -221,6 +221,10 @@ def test_config5_training_step_full_size(seed, timed):
     _say(f"case {wl.name} seed={seed} {'launches as timed: ' + str(timed) if timed else 'staged launches'}: {len(wl.seq_lens)} sequences, "
          f"lengths {sorted(int(x) for x in wl.seq_lens)}")
     host, plan = _run(wl, True, F32, timed)
+    _training_step_checks(wl, host, plan)
+
+
+def _training_step_checks(wl, host, plan, whole_up_to=1300, n_rows=24):
     _tables_exact(wl, plan)
     for name in ("o", "lse", "dq", "dk", "dv"):
         assert np.all(np.isfinite(host[name])), f"{name}: unwritten or non-finite rows"
@@ -230,11 +234,11 @@ def test_config5_training_step_full_size(seed, timed):
     t0 = time.time()
     for s, L in enumerate(wl.seq_lens):
         L = int(L)
-        if L <= 1300:
+        if L <= whole_up_to:
             _whole_seq_check(wl, host, s, accs, True, koff, qrow)
         else:
             _tail_check(wl, host, s, 96, accs, koff, qrow)
-            _rows_check(wl, host, s, rng.integers(0, L - 96, size=24), accs, True, koff, qrow)
+            _rows_check(wl, host, s, rng.integers(0, L - 96, size=n_rows), accs, True, koff, qrow)
         _say(f"  seq {s} (L={L}) checked, {time.time() - t0:.0f} s")
     accs["o"].check()
     accs["lse"].check(TOL_LSE, None)
@@ -242,6 +246,21 @@ def test_config5_training_step_full_size(seed, timed):
     accs["dk"].check()
     accs["dv"].check()
     _gradient_sum_properties(wl, host, koff)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("block,coalesce", [(4096, 1), (4096, 16), (8192, 1), (8192, 16)])
+def test_training_step_with_large_blocks(block, coalesce):
+    """The block sizes at the upper end of the block-size sweep (the paper's system runs 4K-token blocks): the
+    training batch cut into 4096- and 8192-token blocks, one partial per KV block (c = 1: the merge runs) and
+    coalesce degree 16, forward and backward in the timed launch configuration."""
+    wl = workloads.make_workload(5, 0)
+    wl.block_size, wl.coalesce = block, coalesce
+    wl.name += f"-block{block}-c{coalesce}"
+    _say(f"case {wl.name}: {len(wl.seq_lens)} sequences")
+    host, plan = _run(wl, True, F32, True)
+    assert plan["q_blocks"][:, 3].max() > 2048
+    _training_step_checks(wl, host, plan, whole_up_to=700, n_rows=10)
 
 
 @pytest.mark.timeout(600)

@@ -469,3 +469,35 @@ def test_mfma_probe_runs_and_leaves_checksums():
     tflops = {k: n_cu * 8 * 8000 * 16 * 32768.0 / (v * 1e-3) / 1e12 for k, v in ms.items()}
     # the rates are a printed figure, not an assertion: a shared or throttled box must not turn parity red
     _say(f"pure MFMA stream: zeros {tflops[0]:.0f} TFLOP/s, random {tflops[2]:.0f} TFLOP/s")
+
+
+def test_rate_probes_run():
+    """The other measurement aids of fcp_probe.h (vector work beside the MFMA stream, LDS access patterns, atomic
+    adds): each runs with small counts and leaves the expected trace (atomics: every touched element holds a whole
+    number of additions and their total is the number issued)."""
+    import paper_2605_08524_amd as fcp
+    dev = torch.device("cuda:0")
+    n_cu = fcp.fcp_device_info()["n_compute_units"]
+    out = torch.zeros(8 * n_cu, dtype=torch.float32, device=dev)
+    for valu in (0, 2, 4, 6, 8, 12):
+        fcp.fcp_mfma_valu_probe(2, valu, 50, out)
+    src = torch.zeros(65536, dtype=torch.uint8, device=dev)
+    for mode in range(5):
+        for waves in (4, 8):
+            _say(f"lds probe mode {mode} waves {waves}")
+            fcp.fcp_lds_probe(mode, waves, 50, src, out)
+    torch.cuda.synchronize(dev)
+    assert bool(torch.isfinite(out).all())
+    n_rows, stride = 4096, 256
+    buf = torch.zeros(n_rows * stride, dtype=torch.float32, device=dev)
+    fcp.fcp_atomic_probe(buf, n_rows, stride, 7, 2)
+    torch.cuda.synchronize(dev)
+    total = float(buf.double().sum())
+    assert total == n_cu * 2 * 256 * 7 * 16, total
+    assert bool((buf == buf.round()).all())
+    with pytest.raises(fcp.FcpError):
+        fcp.fcp_lds_probe(5, 8, 10, src, out)
+    with pytest.raises(fcp.FcpError):
+        fcp.fcp_mfma_valu_probe(2, 3, 10, out)
+    with pytest.raises(fcp.FcpError):
+        fcp.fcp_atomic_probe(buf, 100, stride, 7, 2)
