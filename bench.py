@@ -512,6 +512,10 @@ def main():
     ap.add_argument("--bwd", choices=("spill", "recompute"), default="spill",
                     help="backward variant: 'spill' keeps dS in the workspace (FCP_FLAG_BWD_SPILL_DS: D pass, dK/dV kernel that also "
                          "writes dS, streaming dQ kernel); 'recompute' runs the dQ kernel that recomputes S and dP, with D fused in")
+    ap.add_argument("--running-merge", action="store_true",
+                    help="forward-only configurations: run the forward as a loop over execution stages that fold their slots into a "
+                         "running (O, LSE) in place (FCP_FLAG_RUNNING_MERGE; no partial buffers, no merge pass) and report its time "
+                         "beside the one-pass path's")
     ap.add_argument("--heads", default=None, metavar="HQ/HKV",
                     help="override the head counts of the workload, e.g. 64/8 (the head shape of the paper's model)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -675,6 +679,24 @@ def main():
     if args.config == 5 and not args.no_merge_record and not args.heads and args.inputs == "normal":
         # the merge launches nothing in the training configuration (one slot per query block): measured on its own
         out["merge"] = merge_record(wl, dev, stream, max(5, args.steps), out_f32=True)
+    if args.running_merge and not backward:
+        from paper_2605_08524_amd.harness import RunningPath
+        part_bytes = dp.o_part.numel() * dp.o_part.element_size() + dp.lse_part.numel() * 4
+        del dp
+        torch.cuda.empty_cache()
+        rp = RunningPath(wl, dev, stream=stream)
+        rp.fwd()
+        torch.cuda.synchronize(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(2, min(args.steps, 5))
+        e0.record(stream)
+        for _ in range(reps):
+            rp.fwd()
+        e1.record(stream)
+        torch.cuda.synchronize(dev)
+        ms = e0.elapsed_time(e1) / reps
+        out["running_merge"] = {"stages": rp.n_stages, "ms": round(ms, 3), "tflops": round(f_fwd / ms / 1e9, 1), "partial_bytes": 0,
+                                "one_pass_partial_bytes": part_bytes, "one_pass_ms": round(stage_ms["fwd"] + stage_ms["merge"], 3)}
     if not args.no_mfma_probe:
         # context for the roofline, measured after the timed region: the published peak stays the denominator of "frac"
         sus = mfma_sustained(dev, stream)

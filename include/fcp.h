@@ -68,6 +68,14 @@ enum {
                                     backward's seven executed contractions for that much HBM traffic each way.  Set it
                                     before fcp_workspace_bytes / fcp_queue_build and keep it for every call on the
                                     workspace.  Shares whose dS does not fit in memory leave it unset. */
+  FCP_FLAG_RUNNING_MERGE = 32,   /* fcp_block_attn_fwd_out folds the result of every slot into the running (o, lse) in place instead of
+                                    writing a partial: (O, LSE) <- merge((O, LSE), slot result), the two-way form of the reduction that
+                                    fcp_merge_partials does in one go.  One launch handles ONE stage: the problem may hold at most one
+                                    slot per query block (fcp_stage_tables cuts a plan into such stages), launches of successive
+                                    stages go to one stream, and before the first one the caller fills lse with -inf (o is then
+                                    ignored).  Needs FCP_FLAG_O_F32; the partial buffers are not touched and may be NULL; no merge call
+                                    follows.  The worker then holds no partials at all, at the price of reading and writing the
+                                    running result once per stage. */
   FCP_FLAG_DIRECT_SINGLE = 2     /* a query block with ONE slot needs no reduction: fcp_block_attn_fwd_out writes its
                                     result straight to the final o / lse and fcp_merge_partials leaves it alone.
                                     Set it before fcp_workspace_bytes / fcp_queue_build and keep it for every call
@@ -117,6 +125,25 @@ int fcp_plan_blocks(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
                     fcp_pair* pairs, int32_t* n_pairs,
                     fcp_slot* slots, int32_t* n_slots,
                     int32_t* n_slot_rows);
+
+/*
+ * fcp_stage_tables -- the tables of one execution stage of a plan (host, integer only).
+ *
+ * Paper: section "Communication Planner": a worker runs its stages one after the other (the KV blocks of a stage
+ * arrive while the previous stage computes) and reduces each stage's result into what it has so far.  Stage k of a
+ * plan = the k-th slot of every query block that has one.  The stage's tables describe the same blocks with only
+ * those slots: pairs keep their (q_blk, kv_blk, kind) and point at the renumbered slots; a slot's row_start is its
+ * query block's tok_start, so that a partial buffer of the stage has the layout of the final output
+ * (n_slot_rows = all query tokens).  Together with the plan's block tables they form a valid fcp_problem.
+ * pairs / slots / q_blocks: the plan's tables (host).  stage >= 0.
+ * stage_pairs / stage_slots: host, caller-allocated; *n_stage_pairs / *n_stage_slots hold the capacities on entry
+ * and the counts on return (NULL tables = size query; too small = FCP_ERR_BUFFER_TOO_SMALL with the counts written).
+ * *n_stages = the largest number of slots any query block has (stages beyond it are empty, which is not an error).
+ */
+int fcp_stage_tables(const fcp_pair* pairs, int32_t n_pairs, const fcp_slot* slots, int32_t n_slots,
+                     const fcp_block* q_blocks, int32_t n_q_blocks, int32_t stage,
+                     fcp_pair* stage_pairs, int32_t* n_stage_pairs, fcp_slot* stage_slots, int32_t* n_stage_slots,
+                     int32_t* n_stages);
 
 /*
  * fcp_workspace_bytes -- size of the device workspace that fcp_queue_build fills for `p`.

@@ -381,6 +381,28 @@ def merge_partials(o_part, lse_part, plan):
     return o, lse
 
 
+def stage_tables(plan, stage):
+    """The tables of one execution stage (section "Communication Planner": a worker runs its
+    stages one after the other and reduces each stage's result into what it has so far).  Stage
+    k = the k-th slot of every query block that has one; its slots are renumbered, its pairs
+    point at them, and a slot's rows are the rows of its query block in the Q buffer (a partial
+    buffer of one stage has the layout of the final output).  Returns (pairs [n,4], slots [n,4],
+    n_stages) with n_stages = the largest number of slots of any query block."""
+    pairs, slots = [], []
+    local = {}
+    most = 0
+    for qb, p0, npairs, _ in (tuple(int(x) for x in row) for row in plan["slots"]):
+        k = local.get(qb, 0)
+        local[qb] = k + 1
+        most = max(most, k + 1)
+        if k != stage:
+            continue
+        slots.append((qb, len(pairs), npairs, int(plan["q_blocks"][qb][2])))
+        for q, kv, kind, _ in plan["pairs"][p0:p0 + npairs]:
+            pairs.append((int(q), int(kv), int(kind), len(slots) - 1))
+    return (np.asarray(pairs, dtype=np.int32).reshape(-1, 4), np.asarray(slots, dtype=np.int32).reshape(-1, 4), most)
+
+
 # --------------------------------------------------------------------------
 # FLOP model used for the reported throughput
 # --------------------------------------------------------------------------

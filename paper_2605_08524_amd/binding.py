@@ -29,9 +29,10 @@ FCP_FLAG_DIRECT_SINGLE = 2
 FCP_FLAG_PART_BF16 = 4
 FCP_FLAG_GRAD_BF16 = 8
 FCP_FLAG_BWD_SPILL_DS = 16
+FCP_FLAG_RUNNING_MERGE = 32
 
 EXPORTS = (
-    "fcp_plan_blocks", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
+    "fcp_plan_blocks", "fcp_stage_tables", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_block_attn_fwd_static",
     "fcp_last_error", "fcp_device_info", "fcp_mfma_probe", "fcp_mfma_valu_probe", "fcp_lds_probe", "fcp_atomic_probe",
@@ -72,6 +73,8 @@ def _load():
     i32p = C.POINTER(C.c_int32)
     lib.fcp_plan_blocks.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32,
                                     C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, i32p]
+    lib.fcp_stage_tables.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                     C.c_void_p, i32p, C.c_void_p, i32p, i32p]
     lib.fcp_workspace_bytes.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_size_t)]
     lib.fcp_queue_build.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fcp_block_attn_fwd.argtypes = [C.POINTER(_Problem)] + [C.c_void_p] * 7
@@ -154,6 +157,22 @@ def fcp_plan_blocks(seq_lens, block_size, causal=1, coalesce=0, q_owned=None):
                                 tabs[3].ctypes.data, C.byref(counts[3]), C.byref(counts[4])))
     tabs = [t[: c.value] for t, c in zip(tabs, counts[:4])]
     return dict(kv_blocks=tabs[0], q_blocks=tabs[1], pairs=tabs[2], slots=tabs[3], n_slot_rows=counts[4].value)
+
+
+def fcp_stage_tables(plan, stage):
+    """The plan restricted to one execution stage: returns (stage_plan, n_stages); stage_plan shares the block tables
+    of `plan` and has n_slot_rows = all query tokens."""
+    pairs, slots, qb = (_i32(plan[k]).reshape(-1, 4) for k in ("pairs", "slots", "q_blocks"))
+    n_p, n_s, n_st = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    args = [pairs.ctypes.data if len(pairs) else None, len(pairs), slots.ctypes.data if len(slots) else None, len(slots),
+            qb.ctypes.data if len(qb) else None, len(qb), int(stage)]
+    _check(_lib.fcp_stage_tables(*args, None, C.byref(n_p), None, C.byref(n_s), C.byref(n_st)))
+    sp = np.zeros((max(1, n_p.value), 4), dtype=np.int32)
+    ss = np.zeros((max(1, n_s.value), 4), dtype=np.int32)
+    _check(_lib.fcp_stage_tables(*args, sp.ctypes.data, C.byref(n_p), ss.ctypes.data, C.byref(n_s), C.byref(n_st)))
+    out = dict(plan)
+    out.update(pairs=sp[: n_p.value], slots=ss[: n_s.value], n_slot_rows=int(qb[:, 3].sum()) if len(qb) else 0)
+    return out, n_st.value
 
 
 class Problem:

@@ -361,6 +361,48 @@ extern "C" int fcp_plan_blocks(const int32_t* seq_lens, int32_t n_seqs, int32_t 
   return FCP_OK;
 }
 
+extern "C" int fcp_stage_tables(const fcp_pair* pairs, int32_t n_pairs, const fcp_slot* slots, int32_t n_slots,
+                                const fcp_block* q_blocks, int32_t n_q_blocks, int32_t stage,
+                                fcp_pair* stage_pairs, int32_t* n_stage_pairs, fcp_slot* stage_slots, int32_t* n_stage_slots,
+                                int32_t* n_stages) {
+  if (n_pairs < 0 || n_slots < 0 || n_q_blocks < 0 || stage < 0 || (n_pairs && !pairs) || (n_slots && !slots) ||
+      (n_q_blocks && !q_blocks) || !n_stage_pairs || !n_stage_slots || !n_stages) {
+    set_error("fcp_stage_tables: invalid argument"); return FCP_ERR_INVALID_ARG;
+  }
+  // pass 1: the stage-th slot of every query block (slots of a block are consecutive), counts
+  int64_t need_pairs = 0, need_slots = 0;
+  int32_t most = 0;
+  for (int s = 0, local = 0; s < n_slots; s++) {
+    const fcp_slot& sl = slots[s];
+    if (sl.q_blk < 0 || sl.q_blk >= n_q_blocks || sl.pair_begin < 0 || sl.n_pairs < 0 || (int64_t)sl.pair_begin + sl.n_pairs > n_pairs ||
+        (s > 0 && sl.q_blk < slots[s - 1].q_blk)) {
+      set_error("fcp_stage_tables: slots[%d] is inconsistent", s); return FCP_ERR_INVALID_ARG;
+    }
+    local = (s > 0 && slots[s - 1].q_blk == sl.q_blk) ? local + 1 : 0;
+    most = std::max(most, local + 1);
+    if (local == stage) { need_slots++; need_pairs += sl.n_pairs; }
+  }
+  const int32_t cap_p = *n_stage_pairs, cap_s = *n_stage_slots;
+  *n_stage_pairs = (int32_t)need_pairs; *n_stage_slots = (int32_t)need_slots; *n_stages = most;
+  if (!stage_pairs && !stage_slots) return FCP_OK;
+  if (!stage_pairs || !stage_slots) { set_error("fcp_stage_tables: pass both tables or none"); return FCP_ERR_INVALID_ARG; }
+  if (cap_p < need_pairs || cap_s < need_slots) {
+    set_error("fcp_stage_tables: table capacity too small (need %lld pairs, %lld slots)", (long long)need_pairs, (long long)need_slots);
+    return FCP_ERR_BUFFER_TOO_SMALL;
+  }
+  int32_t np = 0, ns = 0;
+  for (int s = 0, local = 0; s < n_slots; s++) {
+    const fcp_slot& sl = slots[s];
+    local = (s > 0 && slots[s - 1].q_blk == sl.q_blk) ? local + 1 : 0;
+    if (local != stage) continue;
+    stage_slots[ns] = {sl.q_blk, np, sl.n_pairs, q_blocks[sl.q_blk].tok_start};
+    for (int i = sl.pair_begin; i < sl.pair_begin + sl.n_pairs; i++)
+      stage_pairs[np++] = {pairs[i].q_blk, pairs[i].kv_blk, pairs[i].kind, ns};
+    ns++;
+  }
+  return FCP_OK;
+}
+
 extern "C" int fcp_workspace_bytes(const fcp_problem* p, size_t* bytes) {
   if (!bytes) { set_error("fcp_workspace_bytes: bytes is NULL"); return FCP_ERR_INVALID_ARG; }
   int rc = validate_problem(p);

@@ -265,6 +265,7 @@ struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
   void* o_part; float* lse_part; int32_t part_is_bf16;
   void* o; float* lse; int32_t o_is_f32;     // final outputs for query blocks with a single slot (or NULL)
+  int32_t running;                            // fold every slot into the running (o, lse) in place (fp32 o)
   WsHeader* hdr; const DevPair* pairs; const QItem* items;
   int32_t n_q_heads, n_kv_heads;
   float scale_log2;   // softmax scale * log2(e)
@@ -589,7 +590,32 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     // ---- epilogue: normalise, write the partial (fp32) and its LSE
     const float l_tot = l_run + xor32(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (row_ok) {
+    if (row_ok && a.running) {
+      // Two-way reduction in place: the running (O, LSE) of this row and head, as the earlier stages left it, and
+      // this slot's (o / l_tot, lse_s) combine with weights exp(LSE - m); a running LSE of -inf means "nothing
+      // yet" (whatever O holds then is ignored).  One writer per row and launch; stages are ordered by the stream.
+      const int64_t row = (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row);
+      float* op = reinterpret_cast<float*>(a.o) + row * q_row_stride + (int64_t)head * D;
+      float* lp = a.lse + row * a.n_q_heads + head;
+      const float lse_s = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      const float lse_o = *lp;
+      const float m = fmaxf(lse_o, lse_s);
+      const float w_o = lse_o == -INFINITY ? 0.f : __expf(lse_o - m);
+      const float w_s = lse_s == -INFINITY ? 0.f : __expf(lse_s - m);
+      const float tot = w_o + w_s;
+      const float c_o = tot > 0.f ? w_o / tot : 0.f, c_s = tot > 0.f ? w_s / tot * inv : 0.f;
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x4* ptr = reinterpret_cast<f32x4*>(op + dt * 32 + 8 * q4 + 4 * g);
+          f32x4 old = *ptr;
+          if (lse_o == -INFINITY) old = f32x4{0.f, 0.f, 0.f, 0.f};
+          const f32x4 cur = {o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]};
+          *ptr = old * c_o + cur * c_s;
+        }
+      if (g == 0) *lp = tot > 0.f ? m + __logf(tot) : -INFINITY;
+    } else if (row_ok) {
       // the only slot of its query block: this is the final result, not a partial
       const bool to_final = it.to_final != 0;
       const int64_t row = to_final ? (int64_t)((sub ? it.q_start[1] : it.q_start[0]) + my_row) : (int64_t)((sub ? it.out_row[1] : it.out_row[0]) + my_row);
@@ -1704,8 +1730,23 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
   int rc = layout_for(p, workspace, &L);
   if (rc) return rc;
   if (L.n_fwd_items == 0) return FCP_OK;
-  if (!q || !k || !v || !workspace || (p->n_slot_rows && (!o_part || !lse_part))) { set_error("%s: NULL pointer", who); return FCP_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !workspace || (p->n_slot_rows && !(p->flags & FCP_FLAG_RUNNING_MERGE) && (!o_part || !lse_part))) {
+    set_error("%s: NULL pointer", who); return FCP_ERR_INVALID_ARG;
+  }
   const bool direct = (p->flags & FCP_FLAG_DIRECT_SINGLE) != 0;
+  const bool running = (p->flags & FCP_FLAG_RUNNING_MERGE) != 0;
+  if (running) {
+    if (!o || !lse || !(p->flags & FCP_FLAG_O_F32)) {
+      set_error("%s: FCP_FLAG_RUNNING_MERGE needs the running o (fp32: FCP_FLAG_O_F32) and lse (call fcp_block_attn_fwd_out)", who);
+      return FCP_ERR_INVALID_ARG;
+    }
+    for (int s = 1; s < p->n_slots; s++)
+      if (p->slots[s].q_blk == p->slots[s - 1].q_blk) {
+        set_error("%s: FCP_FLAG_RUNNING_MERGE takes one stage per launch, but query block %d has several slots (see fcp_stage_tables)",
+                  who, p->slots[s].q_blk);
+        return FCP_ERR_INVALID_ARG;
+      }
+  }
   if (direct && (!o || !lse)) {
     set_error("%s: FCP_FLAG_DIRECT_SINGLE needs the final o and lse (call fcp_block_attn_fwd_out)", who);
     return FCP_ERR_INVALID_ARG;
@@ -1714,7 +1755,8 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.o_part = o_part; a.lse_part = lse_part; a.part_is_bf16 = (p->flags & FCP_FLAG_PART_BF16) ? 1 : 0;
-  a.o = direct ? o : nullptr; a.lse = direct ? lse : nullptr;
+  a.o = (direct || running) ? o : nullptr; a.lse = (direct || running) ? lse : nullptr;
+  a.running = running ? 1 : 0;
   a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;
   a.hdr = reinterpret_cast<WsHeader*>(ws);
   a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);

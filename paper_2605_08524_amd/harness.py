@@ -105,3 +105,42 @@ def run_path(wl, device, backward=False, flags=0, softmax_scale=0.0):
         out.update(dq=dp.dq[: p.t_q].float().cpu().numpy(), dk=dp.dk[: p.t_kv].float().cpu().numpy(),
                    dv=dp.dv[: p.t_kv].float().cpu().numpy())
     return out
+
+
+class RunningPath:
+    """The forward as a loop over execution stages with a running result (FCP_FLAG_RUNNING_MERGE): stage k = the k-th
+    slot of every query block; each stage is one fcp_block_attn_fwd_out launch that folds its slots into (o, lse) in
+    place.  No partial buffers exist.  The stages' tables and work queues are built once, up front."""
+
+    def __init__(self, wl, device, softmax_scale=0.0, stream=None):
+        self.wl, self.device, self.stream = wl, device, stream
+        self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+        _, self.n_stages = B.fcp_stage_tables(self.plan, 0)
+        self.q, self.k, self.v = (to_dev_bf16(x, device) for x in (wl.q(), wl.k(), wl.v()))
+        self.t_q = int(self.plan["q_blocks"][:, 3].sum()) if len(self.plan["q_blocks"]) else 0
+        self.o = torch.full((max(1, self.t_q), wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device=device)
+        self.lse = torch.empty((max(1, self.t_q), wl.n_q_heads), dtype=torch.float32, device=device)
+        self.stages = []
+        for st in range(self.n_stages):
+            sp, _ = B.fcp_stage_tables(self.plan, st)
+            prob = B.Problem(sp, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, softmax_scale,
+                             B.FCP_FLAG_RUNNING_MERGE | B.FCP_FLAG_O_F32)
+            nbytes = B.fcp_workspace_bytes(prob)
+            ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+            ws_ptr = ws.data_ptr() + (-ws.data_ptr()) % 256
+            B.fcp_queue_build(prob, ws_ptr, nbytes, stream)
+            self.stages.append((prob, ws, ws_ptr))
+
+    def fwd(self):
+        self.lse.fill_(float("-inf"))        # "nothing yet": the first stage of every row then ignores what o holds
+        for prob, _, ws_ptr in self.stages:
+            B.fcp_block_attn_fwd_out(prob, self.q, self.k, self.v, None, None, self.o, self.lse, ws_ptr, self.stream)
+
+
+def run_running_forward(wl, device, softmax_scale=0.0, stream=None):
+    """One pass of the staged forward with a running result; returns host copies of o and lse, the plan and the
+    number of stages."""
+    rp = RunningPath(wl, device, softmax_scale, stream)
+    rp.fwd()
+    torch.cuda.synchronize(device)
+    return dict(o=rp.o[:rp.t_q].cpu().numpy(), lse=rp.lse[:rp.t_q].cpu().numpy(), plan=rp.plan, n_stages=rp.n_stages)

@@ -283,9 +283,45 @@ def test_config2_forward_full_size_bf16_output():
     accs["lse"].check(TOL_LSE, None)
 
 
+_WL3 = []
+
+
+def _config3():
+    """The long-sequence share, generated once for the tests that use it (a minute of host time)."""
+    if not _WL3:
+        _WL3.append(workloads.make_workload(3, 0))
+    return _WL3[0]
+
+
+@pytest.mark.timeout(1200)
+def test_config3_long_sequence_share_running_merge():
+    """The long-sequence share without any partial buffer: about 32 stages (16 KV blocks each), every stage one launch
+    that folds its slots into the running (O, LSE) in place; sampled rows against the oracle."""
+    from paper_2605_08524_amd.harness import run_running_forward
+    wl = _config3()
+    _say(f"case {wl.name} with a running result: 1M-token sequence, {len(wl.q_owned)} owned query blocks")
+    t0 = time.time()
+    res = run_running_forward(wl, torch.device("cuda:0"))
+    _say(f"  {res['n_stages']} stages in {time.time() - t0:.1f} s (inputs included)")
+    assert res["n_stages"] == -(-(int(wl.q_owned[:, 1].max()) + 1) // wl.coalesce) >= 30
+    _tables_exact(wl, res["plan"])
+    assert np.all(np.isfinite(res["o"])) and np.all(np.isfinite(res["lse"]))
+    koff, qrow = _seq_geometry(wl)
+    accs = {n: _Acc(n) for n in ("o", "lse")}
+    rng = np.random.default_rng(17)
+    bs = wl.block_size
+    blocks = wl.q_owned[rng.choice(len(wl.q_owned), size=12, replace=False), 1]
+    pos = [int(b) * bs + int(rng.integers(0, bs)) for b in blocks]
+    last = int(wl.q_owned[-1, 1]) * bs
+    pos += [last, last + bs - 1]                        # first and last row of the last owned block (it goes through every stage)
+    _rows_check(wl, res, 0, pos, accs, False, koff, qrow)
+    accs["o"].check()
+    accs["lse"].check(TOL_LSE, None)
+
+
 @pytest.mark.timeout(1200)
 def test_config3_long_sequence_share_sampled():
-    wl = workloads.make_workload(3, 0)
+    wl = _config3()
     _say(f"case {wl.name}: 1M-token sequence, {len(wl.q_owned)} owned query blocks")
     host, plan = _run(wl, False, 0)
     _tables_exact(wl, plan)

@@ -501,3 +501,47 @@ def test_rate_probes_run():
         fcp.fcp_mfma_valu_probe(2, 3, 10, out)
     with pytest.raises(fcp.FcpError):
         fcp.fcp_atomic_probe(buf, 100, stride, 7, 2)
+
+
+@pytest.mark.parametrize("case", range(len(EDGE)))
+def test_edge_cases_running_merge(case):
+    """The forward as a loop over execution stages that fold their slots into a running (O, LSE) in place (no partial
+    buffers, no merge pass): same final outputs as the oracle, and as the oracle's own partials reduced two at a time."""
+    from paper_2605_08524_amd.harness import run_running_forward
+    lens, bs, causal, c, hq, hkv, d, owned = EDGE[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=500 + case, name=f"edge{case}-running")
+    _say(f"case {wl.name}")
+    res = run_running_forward(wl, torch.device("cuda:0"))
+    plan = orc.plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+    assert res["n_stages"] == np.bincount(plan["slots"][:, 0]).max()
+    o_ref, lse_ref = orc.worker_fwd(wl.q(), wl.k(), wl.v(), wl.seq_lens, wl.block_size, wl.causal, wl.q_owned)
+    _check("o", res["o"], o_ref)
+    _check_lse("lse", res["lse"], lse_ref)
+
+
+@pytest.mark.parametrize("coalesce", [1, 2])
+def test_config1_tiny_running_merge(coalesce):
+    from paper_2605_08524_amd.harness import run_running_forward
+    wl = workloads.make_workload(1, 1)
+    wl.coalesce = coalesce
+    _say(f"case {wl.name} c={coalesce}")
+    res = run_running_forward(wl, torch.device("cuda:0"))
+    assert res["n_stages"] > 2
+    o_ref, lse_ref = orc.worker_fwd(wl.q(), wl.k(), wl.v(), wl.seq_lens, wl.block_size, wl.causal)
+    _check("o", res["o"], o_ref)
+    _check_lse("lse", res["lse"], lse_ref)
+    # the one-pass path on the same inputs: same result up to the order of the reduction
+    one = run_path(wl, torch.device("cuda:0"), backward=False, flags=F32)
+    err = float(np.max(np.abs(one["o"] - res["o"])))
+    _say(f"  running vs one-pass merge: max-abs {err:.3e}")
+    assert err <= 1e-5
+
+
+def test_running_merge_rejects_several_slots_per_block():
+    import paper_2605_08524_amd as fcp
+    from paper_2605_08524_amd.harness import DevicePath
+    wl = workloads.custom_workload([600], 128, 1, 1, 4, 4, 64, seed=3, name="running-reject")
+    dp = DevicePath(wl, torch.device("cuda:0"), flags=fcp.FCP_FLAG_RUNNING_MERGE | fcp.FCP_FLAG_O_F32, backward=False)
+    with pytest.raises(fcp.FcpError) as e:
+        dp_fwd = fcp.fcp_block_attn_fwd_out(dp.problem, dp.q, dp.k, dp.v, None, None, dp.o, dp.lse, dp.ws_ptr, None)
+    assert e.value.code == fcp.binding.FCP_ERR_INVALID_ARG

@@ -164,3 +164,35 @@ def test_workload_generators_are_seeded():
     # round-to-nearest-even on a tie
     assert workloads.bf16_bits(np.asarray([1.00390625], dtype=np.float32))[0] == 0x3F80
     assert workloads.bf16_bits(np.asarray([1.01171875], dtype=np.float32))[0] == 0x3F82
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4])
+def test_stage_tables_match_oracle(config):
+    wl = workloads.make_workload(config, 1)
+    if config == 1:
+        wl.coalesce = 2
+    plan = fcp.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+    ref_plan = orc.plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+    _, n_stages = fcp.fcp_stage_tables(plan, 0)
+    assert n_stages == orc.stage_tables(ref_plan, 0)[2]
+    for st in sorted({0, 1, n_stages // 2, n_stages - 1, n_stages}):
+        got, ns = fcp.fcp_stage_tables(plan, st)
+        sp, ss, ref_ns = orc.stage_tables(ref_plan, st)
+        assert ns == ref_ns
+        assert np.array_equal(got["pairs"], sp) and np.array_equal(got["slots"], ss)
+        assert got["n_slot_rows"] == int(ref_plan["q_blocks"][:, 3].sum())
+        if len(ss):
+            prob = fcp.Problem(got, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, 0.0,
+                               binding.FCP_FLAG_RUNNING_MERGE | binding.FCP_FLAG_O_F32)
+            assert fcp.fcp_workspace_bytes(prob) > 0            # a valid problem descriptor
+
+
+def test_stage_tables_errors():
+    plan = fcp.fcp_plan_blocks([300, 50], 128, 1, 1)
+    with pytest.raises(fcp.FcpError) as e:
+        fcp.fcp_stage_tables(plan, -1)
+    assert e.value.code == binding.FCP_ERR_INVALID_ARG
+    bad = dict(plan, slots=plan["slots"][::-1].copy())
+    with pytest.raises(fcp.FcpError) as e:
+        fcp.fcp_stage_tables(bad, 0)
+    assert e.value.code == binding.FCP_ERR_INVALID_ARG

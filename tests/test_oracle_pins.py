@@ -364,3 +364,43 @@ def test_input_generators_do_not_need_the_library():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True)
     assert res.returncode == 0 and res.stdout.strip() == "ok", res.stderr
+
+
+@pytest.mark.parametrize("bs,c,causal", [(4, 1, 1), (5, 2, 1), (3, 3, 0), (8, 0, 1)])
+def test_stages_partition_the_plan_and_reduce_pairwise_to_the_whole(bs, c, causal):
+    """A plan cut into execution stages: every pair lands in exactly one stage, stage k holds the k-th slot of each
+    query block, and folding the stages' partial results one by one into a running (O, LSE), two at a time, gives
+    the whole-sequence result (the reduction of the section "Context Parallelism" is associative)."""
+    rng = np.random.default_rng(12)
+    seq_lens = [13, 1, 8, 0, 21, 5]
+    T, Hq, Hkv, d = sum(seq_lens), 4, 2, 8
+    q, k, v = _bits(rng, T, Hq, d), _bits(rng, T, Hkv, d), _bits(rng, T, Hkv, d)
+    plan = orc.plan_blocks(seq_lens, bs, causal, c)
+    _, _, n_stages = orc.stage_tables(plan, 0)
+    per_block = np.bincount(plan["slots"][:, 0], minlength=len(plan["q_blocks"]))
+    assert n_stages == per_block.max()
+    seen = []
+    run_o = np.zeros((T, Hq, d))
+    run_l = np.full((T, Hq), -np.inf)
+    for st in range(n_stages + 1):
+        sp, ss, _ = orc.stage_tables(plan, st)
+        if st == n_stages:
+            assert len(sp) == 0 and len(ss) == 0
+            break
+        assert len(ss) == int((per_block > st).sum())
+        assert np.array_equal(ss[:, 3], plan["q_blocks"][ss[:, 0], 2])          # rows of the block itself
+        assert np.array_equal(sp[:, 3], np.repeat(np.arange(len(ss)), ss[:, 2]))
+        seen += [tuple(r[:3]) for r in sp]
+        stage_plan = dict(plan, pairs=sp, slots=ss, n_slot_rows=T)
+        op, lp = orc.partial_fwd(q, k, v, stage_plan, bs, causal)
+        # two-way reduction through the same merge: "slot" 0 = the running result, slot 1 = this stage
+        two = dict(plan, slots=np.asarray([(b, 0, 0, r0) for b in ss[:, 0] for r0 in (plan["q_blocks"][b][2], T + plan["q_blocks"][b][2])],
+                                          dtype=np.int32).reshape(-1, 4))
+        mo, ml = orc.merge_partials(np.concatenate([run_o, op]), np.concatenate([run_l, lp]), two)
+        for b in ss[:, 0]:
+            r0, n = int(plan["q_blocks"][b][2]), int(plan["q_blocks"][b][3])
+            run_o[r0:r0 + n], run_l[r0:r0 + n] = mo[r0:r0 + n], ml[r0:r0 + n]
+    assert sorted(seen) == sorted(tuple(r[:3]) for r in plan["pairs"])
+    ow, lw = orc.worker_fwd(q, k, v, seq_lens, bs, causal)
+    assert np.max(np.abs(run_o - ow)) < 1e-12
+    assert np.max(np.abs(run_l - lw)) < 1e-12
