@@ -226,6 +226,38 @@ void count_tiles(QItem* it, const DevPair* dpairs) {
   it->n_tiles = n;
 }
 
+// XCD affinity: groups with the same key (sequence, KV head) become one group (items concatenated in the order the
+// groups came), so that all work that streams the K / V (forward, dQ) or Q / dO (dK/dV) rows of one sequence and KV
+// head runs on one XCD and finds them in that XCD's L2 (measured on the training step: forward -1.2 %, dK/dV -0.6 %,
+// dQ from dS -2 %).  Only done while the largest merged group stays below three quarters of an XCD's fair share:
+// a batch dominated by one sequence keeps the finer groups, which balance better.
+template <class Item>
+void merge_groups_by_key(std::vector<std::vector<Item>>& groups, std::vector<int64_t>& weight, const std::vector<int64_t>& key) {
+  {
+    std::vector<int64_t> k2, w2;
+    int64_t total = 0, largest = 0;
+    for (size_t i = 0; i < groups.size(); i++) {
+      size_t j = 0;
+      while (j < k2.size() && k2[j] != key[i]) j++;
+      if (j == k2.size()) { k2.push_back(key[i]); w2.push_back(0); }
+      w2[j] += weight[i];
+      total += weight[i];
+      largest = std::max(largest, w2[j]);
+    }
+    if (largest * kNumXcd * 4 > total * 3) return;
+  }
+  std::vector<std::vector<Item>> g2;
+  std::vector<int64_t> w2, k2;
+  for (size_t i = 0; i < groups.size(); i++) {
+    size_t j = 0;
+    while (j < k2.size() && k2[j] != key[i]) j++;
+    if (j == k2.size()) { k2.push_back(key[i]); g2.emplace_back(); w2.push_back(0); }
+    g2[j].insert(g2[j].end(), groups[i].begin(), groups[i].end());
+    w2[j] += weight[i];
+  }
+  groups.swap(g2); weight.swap(w2);
+}
+
 // Longest-processing-time assignment of weighted groups to the XCD queues: groups in
 // descending weight, each to the currently lightest queue.  Ties resolve to the lower index.
 template <class Item>
@@ -439,7 +471,7 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
   // heads (2j, 2j+1) of the group on one row tile when G is even, else row tiles (2j, 2j+1) of one head.
   {
     std::vector<std::vector<QItem>> groups;
-    std::vector<int64_t> weight;
+    std::vector<int64_t> weight, gkey;
     groups.reserve((size_t)p->n_slots * p->n_kv_heads);
     std::vector<int32_t> n_slots_of(p->n_q_blocks, 0);
     for (int s = 0; s < p->n_slots; s++) n_slots_of[p->slots[s].q_blk]++;
@@ -491,8 +523,10 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
         }
         groups.push_back(std::move(items));
         weight.push_back(w);
+        gkey.push_back((int64_t)qb.seq * p->n_kv_heads + g);
       }
     }
+    merge_groups_by_key(groups, weight, gkey);
     std::vector<QItem> flat;
     spread_over_xcds(groups, weight, &flat, hdr->fwd_begin);
     if ((int64_t)flat.size() != L.n_fwd_items) { set_error("internal: forward item count mismatch"); return FCP_ERR_INVALID_ARG; }
@@ -517,7 +551,7 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
       std::stable_partition(deps + dep_count[b], deps + dep_count[b + 1],
                             [](const BwdDep& d) { return d.kind != FCP_KIND_DIAG; });
     std::vector<std::vector<BwdItem>> groups;
-    std::vector<int64_t> weight;
+    std::vector<int64_t> weight, gkey;
     groups.reserve((size_t)p->n_kv_blocks * p->n_kv_heads);
     for (int b = 0; b < p->n_kv_blocks; b++) {
       const fcp_block& kb = p->kv_blocks[b];
@@ -542,8 +576,10 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
         }
         groups.push_back(std::move(items));
         weight.push_back(w);
+        gkey.push_back((int64_t)kb.seq * p->n_kv_heads + g);
       }
     }
+    merge_groups_by_key(groups, weight, gkey);
     std::vector<BwdItem> flat;
     spread_over_xcds(groups, weight, &flat, hdr->bwd_begin);
     if ((int64_t)flat.size() != L.n_bwd_items) { set_error("internal: backward item count mismatch"); return FCP_ERR_INVALID_ARG; }
@@ -560,7 +596,7 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
       pn[sl.q_blk] += sl.n_pairs;
     }
     std::vector<std::vector<QItem>> groups;
-    std::vector<int64_t> weight;
+    std::vector<int64_t> weight, gkey;
     groups.reserve((size_t)p->n_q_blocks * p->n_kv_heads);
     for (int b = 0; b < p->n_q_blocks; b++) {
       const fcp_block& qb = p->q_blocks[b];
@@ -607,8 +643,10 @@ int fcp::build_queue_image(const fcp_problem* p, const WsLayout& L, bool forward
         }
         groups.push_back(std::move(items));
         weight.push_back(w);
+        gkey.push_back((int64_t)qb.seq * p->n_kv_heads + g);
       }
     }
+    merge_groups_by_key(groups, weight, gkey);
     std::vector<QItem> flat;
     spread_over_xcds(groups, weight, &flat, hdr->dq_begin);
     if ((int64_t)flat.size() != L.n_dq_items) { set_error("internal: dQ item count mismatch"); return FCP_ERR_INVALID_ARG; }
