@@ -44,7 +44,11 @@ typedef enum {
   FCP_ERR_INFEASIBLE = -5        /* the scheduling problem has no solution under the given limits */
 } fcp_status;
 
-enum { FCP_KIND_FULL = 0, FCP_KIND_DIAG = 1 };
+/* Kind of a pair: which (row, column) entries of query block x KV block are attended.
+ *   FULL: all of them.  DIAG: the same block on both sides under a causal mask: column <= row.
+ *   PACKED_FULL / PACKED_DIAG: the same packed block on both sides (a block that holds several whole short
+ *   sequences, see fcp_segment): FULL / DIAG restricted to entries whose row and column lie in the same member. */
+enum { FCP_KIND_FULL = 0, FCP_KIND_DIAG = 1, FCP_KIND_PACKED_FULL = 2, FCP_KIND_PACKED_DIAG = 3 };
 
 /* One fixed-size block of one sequence (the paper's scheduling, compute and transfer unit). */
 typedef struct { int32_t seq, idx, tok_start, tok_len; } fcp_block;
@@ -52,6 +56,9 @@ typedef struct { int32_t seq, idx, tok_start, tok_len; } fcp_block;
 typedef struct { int32_t q_blk, kv_blk, kind, slot; } fcp_pair;
 /* One execution stage of a query block: up to c consecutive pairs -> one partial (O, LSE). */
 typedef struct { int32_t q_blk, pair_begin, n_pairs, row_start; } fcp_slot;
+/* One member sequence of a packed block: tokens [tok_off, tok_off + tok_len) of KV block kv_blk are the whole
+ * sequence seq.  The members of a block are listed in token order and tile it exactly. */
+typedef struct { int32_t kv_blk, seq, tok_off, tok_len; } fcp_segment;
 
 enum {
   FCP_FLAG_O_F32 = 1,            /* the final O is fp32 instead of bf16 (the backward then reads fp32 O) */
@@ -93,6 +100,8 @@ typedef struct {
   const fcp_block* q_blocks;
   const fcp_pair*  pairs;
   const fcp_slot*  slots;
+  int32_t n_segments;            /* 0 unless the tables come from fcp_plan_blocks_packed */
+  const fcp_segment* segments;   /* members of the packed blocks, by (kv_blk, tok_off); NULL when n_segments is 0 */
 } fcp_problem;
 
 /*
@@ -125,6 +134,41 @@ int fcp_plan_blocks(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
                     fcp_pair* pairs, int32_t* n_pairs,
                     fcp_slot* slots, int32_t* n_slots,
                     int32_t* n_slot_rows);
+
+/*
+ * fcp_plan_blocks_packed -- fcp_plan_blocks in which the short sequences of a scheduling unit share ONE block.
+ *
+ * Paper: section "Block Distributor", sharding policy: sequences shorter than the block size are packed into as few
+ * blocks as possible and computed through the kernel's variable-length path.  Here such a block is one block of the
+ * tables, one slot and one chain of work items for the kernels, and the variable-length path is the mask of the
+ * PACKED pair kinds: a query row sees the keys of its own member sequence only.
+ *
+ * unit_of_block[n]: host; the scheduling unit of every block of the unpacked table (the blocks fcp_block_costs and
+ * fcp_plan_blocks list, by (seq, idx)), as written by fcp_pack_units.  A unit with two or more blocks becomes one
+ * packed block; each of its blocks must be a whole sequence shorter than block_size and their lengths must sum
+ * to at most block_size (FCP_ERR_INVALID_ARG otherwise).  Every other block is planned as by fcp_plan_blocks.
+ * Tables, and what differs from fcp_plan_blocks:
+ *   kv_blocks: in the order of the unpacked table, a packed block standing where its lowest member stood (the other
+ *              members are gone): seq = that member's sequence, idx = 0, tok_len = the sum of the members.  tok_start
+ *              is again the running sum, so the K / V buffers hold the tokens in THIS order: the members of a packed
+ *              block next to each other, in ascending order of their unpacked block index.
+ *   q_blocks : the owned blocks in the same order.  q_owned still lists unpacked (seq, idx) rows; a unit is owned as
+ *              a whole or not at all (FCP_ERR_INVALID_ARG otherwise).
+ *   pairs    : a packed query block has ONE pair, with itself: PACKED_DIAG if causal, else PACKED_FULL; one slot.
+ *   segments : the members of every packed block, by (kv_blk, tok_off); *n_segments = capacity / count as for the
+ *              other tables (a NULL segments pointer with the other four tables NULL is the size query).
+ * With no multi-block unit the four tables equal those of fcp_plan_blocks and *n_segments is 0.
+ */
+int fcp_plan_blocks_packed(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
+                           int32_t causal, int32_t coalesce,
+                           const int32_t* q_owned, int32_t n_q_owned,
+                           const int32_t* unit_of_block,
+                           fcp_block* kv_blocks, int32_t* n_kv_blocks,
+                           fcp_block* q_blocks, int32_t* n_q_blocks,
+                           fcp_pair* pairs, int32_t* n_pairs,
+                           fcp_slot* slots, int32_t* n_slots,
+                           int32_t* n_slot_rows,
+                           fcp_segment* segments, int32_t* n_segments);
 
 /*
  * fcp_stage_tables -- the tables of one execution stage of a plan (host, integer only).

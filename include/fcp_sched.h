@@ -42,8 +42,9 @@ int fcp_block_costs(const int32_t* seq_lens, int32_t n_seqs, int32_t block_size,
  * names no packing rule; this is first-fit decreasing: the blocks of single-block sequences with
  * fewer than block_size tokens, in descending length (equal lengths: lower block index first), each
  * go into the first open unit that still has room for them, else open a new unit.  Units are
- * numbered by their lowest member block.  The kernels need nothing for this: a unit's blocks stay
- * separate ragged blocks of the planner; the unit only makes them travel and get assigned together.
+ * numbered by their lowest member block.  For fcp_plan_blocks a unit's blocks stay separate ragged
+ * blocks (the unit only makes them travel and get assigned together); fcp_plan_blocks_packed takes
+ * unit_of_block and turns every unit of two or more blocks into one block for the kernels.
  * blocks / mem / comp: as written by fcp_block_costs.  unit_of_block[n_blocks]: out.
  * unit_mem / unit_comp: out, summed costs, capacity *n_units on entry (n_blocks always suffices);
  * *n_units: count on return.  Feed unit_mem / unit_comp to fcp_assign_blocks; the owner of block b

@@ -38,6 +38,8 @@ import numpy as np
 
 FULL = 0   # every (row, col) of the pair is attended
 DIAG = 1   # same block on both sides under a causal mask: col <= row
+PACKED_FULL = 2   # same packed block on both sides: FULL restricted to (row, col) of one member sequence
+PACKED_DIAG = 3   # same packed block on both sides: DIAG restricted to (row, col) of one member sequence
 
 
 # --------------------------------------------------------------------------
@@ -128,14 +130,159 @@ def plan_blocks(seq_lens, block_size, causal=1, coalesce=0, q_owned=None):
                 n_slot_rows=int(row))
 
 
+def plan_blocks_packed(seq_lens, block_size, causal=1, coalesce=0, q_owned=None, unit_of_block=None):
+    """plan_blocks with the short sequences of a scheduling unit sharing one block (section "Block
+    Distributor", sharding policy: sequences shorter than the block size are packed into as few
+    blocks as possible and go through the variable-length path).
+
+    `unit_of_block` names the unit of every block of the unpacked table (fcp_sched_oracle.pack_units
+    writes it).  Reading (paper silent on the layout): a unit of two or more blocks -- each a whole
+    sequence shorter than a block, together at most block_size tokens -- becomes ONE block that
+    stands where its lowest member stood, holds its members in ascending order of their unpacked
+    block index and carries that member's seq with idx 0; it has one pair, with itself
+    (PACKED_DIAG under a causal mask, else PACKED_FULL), hence one slot.  Everything else is planned
+    as by plan_blocks.  A unit is owned as a whole or not at all.
+
+    Returns the plan_blocks tables plus
+      segments [n, 4] = (kv_blk, seq, tok_off, tok_len): the members of every packed block.
+    """
+    seq_lens = [int(x) for x in np.asarray(seq_lens).reshape(-1)]
+    bs = int(block_size)
+    c = int(coalesce)
+    if bs <= 0 or c < 0 or any(L < 0 for L in seq_lens):
+        raise ValueError("invalid argument")
+    flat = []               # unpacked blocks: (seq, idx, len)
+    for s, L in enumerate(seq_lens):
+        for i in range(-(-L // bs)):
+            flat.append((s, i, min(bs, L - i * bs)))
+    unit = list(range(len(flat))) if unit_of_block is None else [int(u) for u in np.asarray(unit_of_block).reshape(-1)]
+    if len(unit) != len(flat):
+        raise ValueError("unit_of_block must have one entry per unpacked block")
+    members = {}
+    for b, u in enumerate(unit):
+        members.setdefault(u, []).append(b)
+    for u, bl in members.items():
+        if len(bl) >= 2:
+            if any(flat[b][1] != 0 or flat[b][2] >= bs or seq_lens[flat[b][0]] != flat[b][2] for b in bl):
+                raise ValueError("a packed unit may only hold whole sequences shorter than a block")
+            if sum(flat[b][2] for b in bl) > bs:
+                raise ValueError("a packed unit does not fit into one block")
+    if q_owned is None:
+        owned = set(range(len(flat)))
+    else:
+        rows = [(int(a), int(b)) for a, b in np.asarray(q_owned).reshape(-1, 2)]
+        if any(rows[t] >= rows[t + 1] for t in range(len(rows) - 1)):
+            raise ValueError("q_owned must be strictly increasing in (seq, idx)")
+        index = {(s, i): b for b, (s, i, _) in enumerate(flat)}
+        if any(r not in index for r in rows):
+            raise ValueError("owned block out of range")
+        owned = set(index[r] for r in rows)
+    kv_blocks, q_blocks, segments, pairs, slots = [], [], [], [], []
+    kv_of_flat = {}          # unpacked block -> index in kv_blocks (lowest member for a packed block)
+    tok = 0
+    for b, (s, i, ln) in enumerate(flat):
+        bl = members[unit[b]]
+        if len(bl) >= 2:
+            if b != bl[0]:
+                continue
+            off = 0
+            for m in bl:
+                segments.append((len(kv_blocks), flat[m][0], off, flat[m][2]))
+                off += flat[m][2]
+            ln = off
+        kv_of_flat[b] = len(kv_blocks)
+        kv_blocks.append((s, 0 if len(bl) >= 2 else i, tok, ln))
+        tok += ln
+    nblk = {}
+    first = {}
+    for b, (s, i, _) in enumerate(flat):
+        nblk[s] = nblk.get(s, 0) + 1
+        first.setdefault(s, b)
+    row = qtok = 0
+    for b, (s, i, _) in enumerate(flat):
+        bl = members[unit[b]]
+        packed = len(bl) >= 2
+        if packed:
+            own = [m in owned for m in bl]
+            if any(own) and not all(own):
+                raise ValueError("a packed unit must be owned as a whole")
+            if b != bl[0]:
+                continue
+        if b not in owned:
+            continue
+        kb = kv_of_flat[b]
+        ln = kv_blocks[kb][3]
+        qb = len(q_blocks)
+        q_blocks.append((kv_blocks[kb][0], kv_blocks[kb][1], qtok, ln))
+        qtok += ln
+        if packed:
+            slots.append([qb, len(pairs), 1, row])
+            row += ln
+            pairs.append((qb, kb, PACKED_DIAG if causal else PACKED_FULL, len(slots) - 1))
+            continue
+        js = range(i + 1) if causal else range(nblk[s])
+        for r, j in enumerate(js):
+            if (r == 0) if c == 0 else (r % c == 0):
+                slots.append([qb, len(pairs), 0, row])
+                row += ln
+            pairs.append((qb, kv_of_flat[first[s] + j], DIAG if (causal and j == i) else FULL, len(slots) - 1))
+            slots[-1][2] += 1
+    mk = lambda rows: np.asarray(rows, dtype=np.int32).reshape(-1, 4)
+    return dict(kv_blocks=mk(kv_blocks), q_blocks=mk(q_blocks), pairs=mk(pairs), slots=mk(slots),
+                n_slot_rows=int(row), segments=mk(segments))
+
+
+def packed_row_maps(plan, seq_lens, block_size, q_owned=None):
+    """Where the rows of a packed plan's buffers sit in the sequence-major layout that worker_fwd /
+    worker_bwd use: kv_src[r] = row of the sequence-major K / V buffer held by row r of the plan's
+    K / V buffer; q_src[r] likewise for the Q buffers (sequence-major Q = the owned rows by sequence
+    and position, as _owned_positions orders them)."""
+    seq_lens = [int(x) for x in np.asarray(seq_lens).reshape(-1)]
+    bs = int(block_size)
+    seq_off = np.concatenate([[0], np.cumsum(seq_lens)]).astype(np.int64)
+    seg_of = {}
+    for kb, s, off, ln in plan.get("segments", np.zeros((0, 4), np.int32)):
+        seg_of.setdefault(int(kb), []).append((int(s), int(off), int(ln)))
+    kv_index = {(int(b[0]), int(b[1])): n for n, b in enumerate(plan["kv_blocks"])}
+
+    def block_tokens(s, i, ln, kb):
+        """(seq, position) of every token of a block, in buffer order"""
+        if kb in seg_of:
+            return [(ms, p) for ms, _, mlen in seg_of[kb] for p in range(mlen)]
+        return [(s, i * bs + p) for p in range(ln)]
+
+    kv_src = []
+    for kb, (s, i, _, ln) in enumerate(plan["kv_blocks"]):
+        kv_src += [seq_off[ms] + p for ms, p in block_tokens(int(s), int(i), int(ln), kb)]
+    # sequence-major Q row of (seq, position): rank among the owned rows
+    pos = _owned_positions(seq_lens, bs, q_owned)
+    q_row = {}
+    n = 0
+    for s, pp in enumerate(pos):
+        for p in pp:
+            q_row[(s, int(p))] = n
+            n += 1
+    q_src = []
+    for s, i, _, ln in plan["q_blocks"]:
+        kb = kv_index[(int(s), int(i))]
+        q_src += [q_row[t] for t in block_tokens(int(s), int(i), int(ln), kb)]
+    return np.asarray(kv_src, dtype=np.int64), np.asarray(q_src, dtype=np.int64)
+
+
 def pair_nnz(plan) -> int:
     """Number of unmasked score entries over all pairs (per query head).
-    FULL m x n -> m*n; DIAG m x m -> m(m+1)/2."""
+    FULL m x n -> m*n; DIAG m x m -> m(m+1)/2; the PACKED kinds: the same, member by member."""
+    seg_of = {}
+    for kb, _, _, ln in plan.get("segments", np.zeros((0, 4), np.int32)):
+        seg_of.setdefault(int(kb), []).append(int(ln))
     tot = 0
     for qb, kb, kind, _ in plan["pairs"]:
         m = int(plan["q_blocks"][qb][3])
         n = int(plan["kv_blocks"][kb][3])
-        tot += m * (m + 1) // 2 if kind == DIAG else m * n
+        if kind in (PACKED_FULL, PACKED_DIAG):
+            tot += sum(x * (x + 1) // 2 if kind == PACKED_DIAG else x * x for x in seg_of[int(kb)])
+        else:
+            tot += m * (m + 1) // 2 if kind == DIAG else m * n
     return tot
 
 

@@ -404,3 +404,115 @@ def test_stages_partition_the_plan_and_reduce_pairwise_to_the_whole(bs, c, causa
     ow, lw = orc.worker_fwd(q, k, v, seq_lens, bs, causal)
     assert np.max(np.abs(run_o - ow)) < 1e-12
     assert np.max(np.abs(run_l - lw)) < 1e-12
+
+
+def _visibility_from_tables(plan):
+    """Dense count of how often every (Q-buffer row, KV-buffer row) entry is attended, read off the
+    tables by the definitions of the pair kinds alone."""
+    kvb, qb = plan["kv_blocks"], plan["q_blocks"]
+    seg_id = {}
+    for n, (kb, _, off, ln) in enumerate(plan["segments"]):
+        ids = seg_id.setdefault(int(kb), np.full(int(kvb[kb][3]), -1))
+        assert np.all(ids[off:off + ln] == -1)
+        ids[off:off + ln] = n
+    got = np.zeros((int(qb[:, 3].sum()), int(kvb[:, 3].sum())), dtype=np.int64)
+    for q_, k_, kind, _ in plan["pairs"]:
+        _, _, qs, ql = qb[q_]
+        _, _, ks, kl = kvb[k_]
+        blk = np.ones((ql, kl), dtype=np.int64)
+        if kind in (orc.DIAG, orc.PACKED_DIAG):
+            assert ql == kl
+            blk = np.tril(blk)
+        if kind in (orc.PACKED_FULL, orc.PACKED_DIAG):
+            ids = seg_id[int(k_)]
+            assert ql == kl and np.all(ids >= 0)          # members tile the block
+            blk = blk * (ids[:, None] == ids[None, :])
+        else:
+            assert int(k_) not in seg_id                   # a packed block only pairs with itself
+        got[qs:qs + ql, ks:ks + kl] += blk
+    return got
+
+
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("owned_kind", ["all", "subset"])
+def test_packed_planner_brute_force_coverage(causal, owned_kind):
+    """The packed plan attends exactly the entries the definition names (same sequence, key not after the query
+    under a causal mask), each once, once its rows are mapped back to the sequence-major order."""
+    from oracle import fcp_sched_oracle as sch
+    seq_lens, bs = [3, 10, 2, 0, 5, 17, 4, 1, 6, 8, 3], 8
+    flat = orc.plan_blocks(seq_lens, bs, causal, 0)["kv_blocks"]
+    unit, _, _ = sch.pack_units(flat, [int(b[3]) for b in flat], [0] * len(flat), bs)
+    assert max(np.bincount(unit)) >= 3                     # the case has real packing
+    q_owned = None
+    if owned_kind == "subset":
+        # drop the unit of block 0 as a whole, and one block of a long sequence
+        drop = {b for b in range(len(flat)) if unit[b] == unit[0]} | {2}
+        q_owned = np.asarray([(int(flat[b][0]), int(flat[b][1])) for b in range(len(flat)) if b not in drop], dtype=np.int32)
+    plan = orc.plan_blocks_packed(seq_lens, bs, causal, 2, q_owned, unit)
+    kv_src, q_src = orc.packed_row_maps(plan, seq_lens, bs, q_owned)
+    T = sum(seq_lens)
+    assert np.array_equal(np.sort(kv_src), np.arange(T))   # a permutation of the tokens
+    assert len(set(q_src.tolist())) == len(q_src) == int(plan["q_blocks"][:, 3].sum())
+    seq_of = np.repeat(np.arange(len(seq_lens)), seq_lens)
+    pos_of = np.concatenate([np.arange(L) for L in seq_lens])
+    # sequence-major Q rows: the owned tokens by (sequence, position)
+    own_tok = np.arange(T) if q_owned is None else np.concatenate(
+        [np.arange(bs * i, min(bs * (i + 1), seq_lens[s])) + int(np.sum(seq_lens[:s])) for s, i in q_owned])
+    qs_, ks_ = own_tok[q_src], kv_src
+    want = seq_of[qs_][:, None] == seq_of[ks_][None, :]
+    if causal:
+        want &= pos_of[ks_][None, :] <= pos_of[qs_][:, None]
+    got = _visibility_from_tables(plan)
+    assert np.array_equal(got, want.astype(np.int64))
+    assert orc.pair_nnz(plan) == int(want.sum())
+    # fewer blocks than without packing, one pair and one slot per packed query block
+    assert len(plan["kv_blocks"]) < len(flat)
+    packed_q = [q for q, _, kind, _ in plan["pairs"] if kind >= orc.PACKED_FULL]
+    assert len(packed_q) == len(set(packed_q)) and len(packed_q) >= 1
+    assert np.array_equal(plan["kv_blocks"][:, 2], np.concatenate([[0], np.cumsum(plan["kv_blocks"][:-1, 3])]))
+    assert np.array_equal(plan["q_blocks"][:, 2], np.concatenate([[0], np.cumsum(plan["q_blocks"][:-1, 3])]))
+    assert np.array_equal(plan["pairs"][:, 3], np.repeat(np.arange(len(plan["slots"])), plan["slots"][:, 2]))
+
+
+def test_packed_planner_without_units_is_the_plain_planner():
+    seq_lens, bs = [10, 3, 0, 17, 4, 1], 4
+    for causal in (0, 1):
+        for c in (0, 2):
+            a = orc.plan_blocks(seq_lens, bs, causal, c)
+            b = orc.plan_blocks_packed(seq_lens, bs, causal, c, None, None)
+            for key in ("kv_blocks", "q_blocks", "pairs", "slots"):
+                assert np.array_equal(a[key], b[key])
+            assert a["n_slot_rows"] == b["n_slot_rows"] and len(b["segments"]) == 0
+            b2 = orc.plan_blocks_packed(seq_lens, bs, causal, c, None, np.arange(len(a["kv_blocks"])))
+            assert all(np.array_equal(a[k], b2[k]) for k in ("kv_blocks", "q_blocks", "pairs", "slots"))
+
+
+def test_packed_planner_rejects_bad_units():
+    with pytest.raises(ValueError):      # a block of a long sequence in a unit with another block
+        orc.plan_blocks_packed([10, 2], 4, 1, 0, None, [0, 1, 2, 2])
+    with pytest.raises(ValueError):      # the unit does not fit into a block
+        orc.plan_blocks_packed([3, 3], 4, 1, 0, None, [0, 0])
+    with pytest.raises(ValueError):      # a unit owned in part
+        orc.plan_blocks_packed([2, 1, 5], 4, 1, 0, [(0, 0), (2, 0)], [0, 0, 1, 2])
+    with pytest.raises(ValueError):      # one entry per unpacked block
+        orc.plan_blocks_packed([2, 1], 4, 1, 0, None, [0])
+
+
+def test_packed_attention_is_the_per_sequence_definition():
+    """What a packed block computes is pinned to the plain definition without any planner: attention over the
+    concatenated tokens of the members with a same-member (and causal) mask equals attention of every member by itself."""
+    rng = np.random.default_rng(5)
+    lens, H, d = [3, 1, 4], 2, 8
+    q, k, v = (_rand(rng, sum(lens), H, d) for _ in range(3))
+    member = np.repeat(np.arange(len(lens)), lens)
+    for causal in (True, False):
+        o_ref = np.zeros_like(q)
+        lse_ref = np.zeros((sum(lens), H))
+        off = 0
+        for L in lens:
+            o_ref[off:off + L], lse_ref[off:off + L] = orc.attention_fwd_seq(q[off:off + L], k[off:off + L], v[off:off + L], causal, 0.3)
+            off += L
+        for i in range(sum(lens)):       # row by row over the visible keys of the concatenation
+            vis = [j for j in range(sum(lens)) if member[j] == member[i] and (not causal or j <= i)]
+            o, lse = orc.attention_fwd_seq(q[i:i + 1], k[vis], v[vis], False, 0.3)
+            assert np.allclose(o[0], o_ref[i], atol=1e-12) and np.allclose(lse[0], lse_ref[i], atol=1e-12)
