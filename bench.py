@@ -58,6 +58,12 @@ def pair_flops(plan, n_q_heads, head_dim):
     m = qlen[pr[:, 0]]
     n = klen[pr[:, 1]]
     nnz = int(((pr[:, 2] == 0) * m * n + (pr[:, 2] == 1) * (m * (m + 1) // 2)).sum())
+    if "segments" in plan and len(plan["segments"]):
+        # packed blocks: their one pair attends every member sequence by itself
+        causal = {int(kb): int(kind) & 1 for _, kb, kind, _ in pr if kind >= 2}
+        for kb, _, _, ln in plan["segments"]:
+            if int(kb) in causal:
+                nnz += int(ln) * (int(ln) + 1) // 2 if causal[int(kb)] else int(ln) * int(ln)
     return 4 * head_dim * n_q_heads * nnz, 10 * head_dim * n_q_heads * nnz, nnz
 
 
@@ -500,6 +506,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload: 5 = training step (default), 2/3/4 = forward only")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--packed", action="store_true",
+                    help="plan with fcp_plan_blocks_packed: the short sequences of a scheduling unit share one block")
+    ap.add_argument("--with-backward", action="store_true", help="time the backward too on configs 2 to 4")
+    ap.add_argument("--short-mix", action="store_true",
+                    help="workload: 64K tokens of sequences shorter than a block (uniform [16, 256), block 1024) instead of --config; "
+                         "with and without --packed it shows what sharing blocks is worth to the kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--inputs", choices=("normal", "zeros", "half"), default="normal",
                     help="operand values: the workload's N(0,1) tensors (default: the benchmark), or all zeros / all 0.5 "
@@ -558,11 +570,11 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = workloads.make_workload(args.config, args.seed)
+    wl = workloads.short_mix_workload(args.seed) if args.short_mix else workloads.make_workload(args.config, args.seed)
     if args.heads:
         wl.n_q_heads, wl.n_kv_heads = (int(x) for x in args.heads.split("/"))
         wl.name += f"-heads{wl.n_q_heads}x{wl.n_kv_heads}"
-    backward = args.config == 5
+    backward = (args.config == 5 and not args.short_mix) or args.with_backward
     stream = torch.cuda.current_stream(dev)
     t0 = time.perf_counter()
     # a query block with one slot needs no reduction: the forward writes it straight to the final O / LSE
@@ -572,7 +584,9 @@ def main():
     spill = backward and args.bwd == "spill"
     if spill:
         flags |= FCP_FLAG_BWD_SPILL_DS
-    dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream)
+    dp = DevicePath(wl, dev, flags=flags, backward=backward, stream=stream, packed=args.packed)
+    if args.packed:
+        wl.name += "-packed"
     if args.inputs != "normal":
         for t in (dp.q, dp.k, dp.v) + ((dp.d_o,) if backward else ()):
             t.fill_(0.0 if args.inputs == "zeros" else 0.5)
@@ -626,7 +640,7 @@ def main():
     kernel_flops = {"fwd": 4 * unit, "bwd_dkdv": 8 * unit, "bwd_dq": (2 if spill else 6) * unit}
     kernel_name = {"fwd": "fwd_kernel", "bwd_dkdv": "dkdv_kernel", "bwd_dq": "dq_ds_kernel" if spill else "dq_kernel"}
     tf = "true" if spill else "false"
-    kernel_instance = {"fwd": f"fcp::fwd_kernel<{wl.head_dim}>", "bwd_dkdv": f"fcp::dkdv_kernel<{wl.head_dim}, false, {tf}>",
+    kernel_instance = {"fwd": f"fcp::fwd_kernel<{wl.head_dim}, {'true' if args.packed else 'false'}>", "bwd_dkdv": f"fcp::dkdv_kernel<{wl.head_dim}, false, {tf}>",
                        "bwd_dq": f"fcp::dq_ds_kernel<{wl.head_dim}, false>" if spill else f"fcp::dq_kernel<{wl.head_dim}, true, false>"}
     cands = [k for k in kernel_flops if k in stage_ms]
     dom = max(cands, key=lambda k: stage_ms[k])
@@ -655,6 +669,8 @@ def main():
             "block_size": wl.block_size, "coalesce": wl.coalesce, "n_q_heads": wl.n_q_heads,
             "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "n_seqs": int(len(wl.seq_lens)),
             "n_pairs": int(len(dp.plan["pairs"])), "n_slots": int(len(dp.plan["slots"])),
+            "n_q_blocks": int(len(dp.plan["q_blocks"])), "packed_members": int(len(dp.plan.get("segments", ()))),
+            "fwd_items": int(sum(-(-int(dp.plan["q_blocks"][qb][3]) // 128) for qb in dp.plan["slots"][:, 0]) * (wl.n_q_heads // 2 if (wl.n_q_heads // wl.n_kv_heads) % 2 == 0 else wl.n_q_heads)),
             "nnz_per_head": nnz, "o_dtype": "f32" if backward else "bf16", "parallelism": "single-gpu",
             "backward": (args.bwd if backward else None), "workspace_bytes": dp.ws_bytes,
         },
@@ -676,7 +692,7 @@ def main():
         "grid": info, "setup_s": round(setup_s, 2),
         "host_ms": {"plan_blocks": round(dp.plan_ms, 3), "queue_build": round(dp.queue_build_ms, 3)},
     }
-    if args.config == 5 and not args.no_merge_record and not args.heads and args.inputs == "normal":
+    if args.config == 5 and not args.short_mix and not args.packed and not args.no_merge_record and not args.heads and args.inputs == "normal":
         # the merge launches nothing in the training configuration (one slot per query block): measured on its own
         out["merge"] = merge_record(wl, dev, stream, max(5, args.steps), out_f32=True)
     if args.running_merge and not backward:

@@ -9,8 +9,8 @@ import importlib
 
 _BINDING_NAMES = (
     "FCP_FLAG_DIRECT_SINGLE", "FCP_FLAG_O_F32", "FCP_FLAG_GRAD_BF16", "FCP_FLAG_PART_BF16", "FCP_FLAG_BWD_SPILL_DS", "FCP_FLAG_RUNNING_MERGE",
-    "FCP_KIND_DIAG", "FCP_KIND_FULL", "FCP_ERR_INFEASIBLE", "FcpError", "Problem",
-    "fcp_plan_blocks", "fcp_stage_tables", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
+    "FCP_KIND_DIAG", "FCP_KIND_FULL", "FCP_KIND_PACKED_FULL", "FCP_KIND_PACKED_DIAG", "FCP_ERR_INFEASIBLE", "FcpError", "Problem",
+    "fcp_plan_blocks", "fcp_plan_blocks_packed", "fcp_stage_tables", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_block_attn_fwd_static",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv",
     "fcp_block_attn_bwd_dq", "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_device_info", "fcp_last_error", "fcp_mfma_probe", "fcp_mfma_valu_probe", "fcp_lds_probe", "fcp_atomic_probe",

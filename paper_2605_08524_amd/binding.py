@@ -23,7 +23,7 @@ FCP_ERR_BUFFER_TOO_SMALL = -2
 FCP_ERR_UNSUPPORTED = -3
 FCP_ERR_HIP = -4
 FCP_ERR_INFEASIBLE = -5
-FCP_KIND_FULL, FCP_KIND_DIAG = 0, 1
+FCP_KIND_FULL, FCP_KIND_DIAG, FCP_KIND_PACKED_FULL, FCP_KIND_PACKED_DIAG = 0, 1, 2, 3
 FCP_FLAG_O_F32 = 1
 FCP_FLAG_DIRECT_SINGLE = 2
 FCP_FLAG_PART_BF16 = 4
@@ -32,7 +32,7 @@ FCP_FLAG_BWD_SPILL_DS = 16
 FCP_FLAG_RUNNING_MERGE = 32
 
 EXPORTS = (
-    "fcp_plan_blocks", "fcp_stage_tables", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
+    "fcp_plan_blocks", "fcp_plan_blocks_packed", "fcp_stage_tables", "fcp_workspace_bytes", "fcp_queue_build", "fcp_block_attn_fwd", "fcp_block_attn_fwd_out",
     "fcp_merge_partials", "fcp_block_attn_bwd", "fcp_bwd_preprocess", "fcp_block_attn_bwd_dkdv", "fcp_block_attn_bwd_dq",
     "fcp_block_attn_bwd_dq_d", "fcp_block_attn_bwd_dq_ds", "fcp_block_attn_fwd_static",
     "fcp_last_error", "fcp_device_info", "fcp_mfma_probe", "fcp_mfma_valu_probe", "fcp_lds_probe", "fcp_atomic_probe",
@@ -54,6 +54,7 @@ class _Problem(C.Structure):
         ("n_kv_blocks", C.c_int32), ("n_q_blocks", C.c_int32), ("n_pairs", C.c_int32), ("n_slots", C.c_int32),
         ("n_slot_rows", C.c_int32),
         ("kv_blocks", C.c_void_p), ("q_blocks", C.c_void_p), ("pairs", C.c_void_p), ("slots", C.c_void_p),
+        ("n_segments", C.c_int32), ("segments", C.c_void_p),
     ]
 
 
@@ -73,6 +74,8 @@ def _load():
     i32p = C.POINTER(C.c_int32)
     lib.fcp_plan_blocks.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32,
                                     C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, i32p]
+    lib.fcp_plan_blocks_packed.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32, i32p,
+                                           C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, C.c_void_p, i32p, i32p, C.c_void_p, i32p]
     lib.fcp_stage_tables.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_void_p, i32p, C.c_void_p, i32p, i32p]
     lib.fcp_workspace_bytes.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_size_t)]
@@ -159,6 +162,29 @@ def fcp_plan_blocks(seq_lens, block_size, causal=1, coalesce=0, q_owned=None):
     return dict(kv_blocks=tabs[0], q_blocks=tabs[1], pairs=tabs[2], slots=tabs[3], n_slot_rows=counts[4].value)
 
 
+def fcp_plan_blocks_packed(seq_lens, block_size, causal=1, coalesce=0, q_owned=None, unit_of_block=None):
+    """fcp_plan_blocks with every scheduling unit of two or more blocks (unit_of_block, from fcp_pack_units) as one
+    packed block.  Returns the fcp_plan_blocks dict plus segments: int32 [n,4] = (kv_blk, seq, tok_off, tok_len)."""
+    sl = _i32(np.asarray(seq_lens).reshape(-1))
+    qo = None if q_owned is None else _i32(np.asarray(q_owned).reshape(-1, 2))
+    ub = None if unit_of_block is None else _i32(np.asarray(unit_of_block).reshape(-1))
+    i32p = C.POINTER(C.c_int32)
+    args = [sl.ctypes.data_as(i32p), len(sl), int(block_size), int(causal), int(coalesce),
+            None if qo is None else qo.ctypes.data_as(i32p), 0 if qo is None else len(qo),
+            None if ub is None else ub.ctypes.data_as(i32p)]
+    counts = [C.c_int32(0) for _ in range(6)]     # kv, q, pairs, slots, slot rows, segments
+
+    def call(tabs):
+        return _lib.fcp_plan_blocks_packed(*args, tabs[0], C.byref(counts[0]), tabs[1], C.byref(counts[1]), tabs[2], C.byref(counts[2]),
+                                           tabs[3], C.byref(counts[3]), C.byref(counts[4]), tabs[4], C.byref(counts[5]))
+    _check(call([None] * 5))
+    sizes = [counts[i].value for i in (0, 1, 2, 3, 5)]
+    tabs = [np.zeros((max(1, n), 4), dtype=np.int32) for n in sizes]
+    _check(call([t.ctypes.data for t in tabs]))
+    tabs = [t[:n] for t, n in zip(tabs, sizes)]
+    return dict(kv_blocks=tabs[0], q_blocks=tabs[1], pairs=tabs[2], slots=tabs[3], n_slot_rows=counts[4].value, segments=tabs[4])
+
+
 def fcp_stage_tables(plan, stage):
     """The plan restricted to one execution stage: returns (stage_plan, n_stages); stage_plan shares the block tables
     of `plan` and has n_slot_rows = all query tokens."""
@@ -184,6 +210,7 @@ class Problem:
         self.pairs = _i32(plan["pairs"]).reshape(-1, 4)
         self.slots = _i32(plan["slots"]).reshape(-1, 4)
         self.n_slot_rows = int(plan["n_slot_rows"])
+        self.segments = _i32(plan["segments"]).reshape(-1, 4) if "segments" in plan else np.zeros((0, 4), dtype=np.int32)
         self.flags = int(flags)
         self.n_q_heads, self.n_kv_heads, self.head_dim = int(n_q_heads), int(n_kv_heads), int(head_dim)
         self.t_q = int(self.q_blocks[:, 3].sum()) if len(self.q_blocks) else 0
@@ -194,7 +221,8 @@ class Problem:
             self.kv_blocks.ctypes.data if len(self.kv_blocks) else None,
             self.q_blocks.ctypes.data if len(self.q_blocks) else None,
             self.pairs.ctypes.data if len(self.pairs) else None,
-            self.slots.ctypes.data if len(self.slots) else None)
+            self.slots.ctypes.data if len(self.slots) else None,
+            len(self.segments), self.segments.ctypes.data if len(self.segments) else None)
 
     @property
     def ref(self):

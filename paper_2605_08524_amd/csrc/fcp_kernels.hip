@@ -267,12 +267,14 @@ struct FwdArgs {
   void* o; float* lse; int32_t o_is_f32;     // final outputs for query blocks with a single slot (or NULL)
   int32_t running;                            // fold every slot into the running (o, lse) in place (fp32 o)
   WsHeader* hdr; const DevPair* pairs; const QItem* items;
+  int32_t* counter; const int32_t* begin; int32_t* done;   // the XCD queues this launch drains (header fields)
+  const uint32_t* q_seg;                      // member bounds per Q-buffer row (packed blocks only)
   int32_t n_q_heads, n_kv_heads;
   float scale_log2;   // softmax scale * log2(e)
 };
 
 // Iterator over the KV tiles of an item's pairs, in pair order.  For a DIAG pair only the
-// columns up to the tile's last query row are visited.
+// columns up to the tile's last query row are visited, for a PACKED pair the item's column range.
 struct TileIter {
   const DevPair* pairs;
   int pair, pair_end, c0, ncols, row_hi;   // row_hi = tile_off + q_rows (first row past the tile)
@@ -284,13 +286,16 @@ struct TileIter {
     const DevPair p = pairs[pair];
     cur.kv_start = __builtin_amdgcn_readfirstlane(p.kv_start); cur.kv_len = __builtin_amdgcn_readfirstlane(p.kv_len);
     cur.kind = __builtin_amdgcn_readfirstlane(p.kind); cur.ds_frag = __builtin_amdgcn_readfirstlane(p.ds_frag);
-    ncols = cur.kind == FCP_KIND_DIAG ? min(cur.kv_len, row_hi) : cur.kv_len;
+    ncols = (cur.kind & 1) ? min(cur.kv_len, row_hi) : cur.kv_len;
   }
-  __device__ __forceinline__ void init(const DevPair* p, int begin, int n, int row_hi_) {
-    pairs = p; pair = begin; pair_end = begin + n; c0 = 0; ncols = 0; row_hi = row_hi_;
+  __device__ __forceinline__ void init(const DevPair* p, const QItem& it) {
+    pairs = p; pair = it.pair_begin; pair_end = it.pair_begin + it.n_pairs; c0 = 0; ncols = 0;
+    row_hi = max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]);
     cur = DevPair{0, 0, 0, 0};
-    more = n > 0;
+    more = it.n_pairs > 0;
     if (more) load_pair();
+    // a PACKED pair is the only pair of its item: the item's column range replaces the pair's, here and nowhere else
+    if (it.col_end > 0) { c0 = it.col_begin; ncols = it.col_end; }
   }
   __device__ __forceinline__ void advance() {
     c0 += kFwdTileN;
@@ -302,11 +307,14 @@ struct TileIter {
   }
 };
 
-// What a wave needs to know about a tile when it masks it: first column, visible length, kind.
+// What a wave needs to know about a tile when it masks it: first column, visible length, kind of its pair.
 // A tile past the end of the item has len = 0: everything is masked.
-struct TileMeta { int c0, len, diag; };
+struct TileMeta { int c0, len, kind; };
 
-template <int D>
+// PACKED: the instance for the items of packed blocks (several short sequences in one block), which have queues of
+// their own and a launch of their own; only it carries the per-row member bounds and the second mask, which cost
+// the other instance 4 % when they were compiled into it.
+template <int D, bool PACKED>
 __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
   constexpr int KC = D / 16;      // k-chunks of the QK^T contraction
   constexpr int DT = D / 32;      // row tiles of O^T
@@ -319,6 +327,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
   constexpr int CPR = D / 8, RPI = 64 / CPR, NDMA = kFwdTileN / RPI / 8;   // LDS-DMA geometry, see issue()
   constexpr int DMA_PER_TILE = 2 * NDMA;
   __shared__ __attribute__((aligned(1024))) unsigned char lds_kv[NB][BUF];
+  __shared__ uint32_t s_seg[512];   // member bounds of each lane's query row in a packed block (written and read by that lane)
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -359,7 +368,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
   __syncthreads();
 
   ItemStream items;
-  if (tid == 0) { items.init(a.hdr->fwd_counter, a.hdr->fwd_begin); items.request(); s_item = items.resolve(); }
+  if (tid == 0) { items.init(a.counter, a.begin); items.request(); s_item = items.resolve(); }
   __syncthreads();
   for (;;) {
     const int item_idx = __builtin_amdgcn_readfirstlane(s_item);   // uniform: tables are read with scalar loads
@@ -375,6 +384,10 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     const int my_limit = tile_off_q + my_row;                // last visible column of a DIAG pair for this lane
     const uint16_t* kbase = a.k + (int64_t)kvh * D;
     const uint16_t* vbase = a.v + (int64_t)kvh * D;
+    // packed block: the columns this lane's row may see, parked in LDS until a tile is masked (rows past the end: none)
+    if constexpr (PACKED) {
+      if (it.col_end > 0) s_seg[tid] = row_ok ? a.q_seg[(sub ? it.q_start[1] : it.q_start[0]) + my_row] : 0u;
+    }
 
     // Q^T fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d per k-chunk.
     bf16x8 qf[KC];
@@ -396,7 +409,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
 
     // number of tiles of the item, and of iterations: tiles + 1 (pipeline fill)
     TileIter ti;                      // names the next tile to LOAD
-    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
+    ti.init(a.pairs, it);
     const int n_it = 1 + it.n_tiles;
 
     // The load of one tile in two parts.  describe(): scalar bookkeeping with branches, run at
@@ -412,7 +425,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         d_v = reinterpret_cast<uint64_t>(vbase + row0);
         const int valid = min(kFwdTileN, ti.cur.kv_len - ti.c0);
         d_lim = (uint32_t)((valid - 1) * kv_row_stride * 2);
-        d_meta = TileMeta{ti.c0, ti.cur.kv_len, ti.cur.kind == FCP_KIND_DIAG ? 1 : 0};
+        d_meta = TileMeta{ti.c0, ti.cur.kv_len, ti.cur.kind};
         ti.advance();
       }
     };
@@ -522,15 +535,29 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
         // readfirstlane: the condition is wave-uniform, but the compiler does not know it and would
         // otherwise run the rare path on every tile as 64 compares and selects
         const int need_mask = __builtin_amdgcn_readfirstlane(
-            (int)(tm.len == 0 || tm.c0 + kFwdTileN > tm.len || (tm.diag && tm.c0 + kFwdTileN - 1 > wave_row_lo)));
+            (int)(tm.len == 0 || tm.c0 + kFwdTileN > tm.len || (PACKED && (tm.kind & 2)) || ((tm.kind & 1) && tm.c0 + kFwdTileN - 1 > wave_row_lo)));
         if (need_mask) {
-          // last visible column for this lane, relative to the tile's first column
-          const int limit = (tm.diag ? min(tm.len - 1, my_limit) : tm.len - 1) - tm.c0 - 4 * g;
+          if (PACKED && __builtin_amdgcn_readfirstlane(tm.kind & 2)) {
+            // packed block: the row sees the columns of its own member (up to itself under a causal mask)
+            const uint32_t sg = s_seg[tid];
+            const int first = (int)(sg & 0xffff) - tm.c0 - 4 * g;
+            const int last = ((tm.kind & 1) ? min((int)(sg >> 16) - 1, my_limit) : (int)(sg >> 16) - 1) - tm.c0 - 4 * g;
 #pragma unroll
-          for (int rt = 0; rt < 2; rt++)
+            for (int rt = 0; rt < 2; rt++)
 #pragma unroll
-            for (int r = 0; r < 16; r++)
-              if (rt * 32 + 8 * (r >> 2) + (r & 3) > limit) sn[rt][r] = -INFINITY;
+              for (int r = 0; r < 16; r++) {
+                const int c = rt * 32 + 8 * (r >> 2) + (r & 3);
+                if (c > last || c < first) sn[rt][r] = -INFINITY;
+              }
+          } else {
+            // last visible column for this lane, relative to the tile's first column
+            const int limit = ((tm.kind & 1) ? min(tm.len - 1, my_limit) : tm.len - 1) - tm.c0 - 4 * g;
+#pragma unroll
+            for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+              for (int r = 0; r < 16; r++)
+                if (rt * 32 + 8 * (r >> 2) + (r & 3) > limit) sn[rt][r] = -INFINITY;
+          }
         }
       }
       if constexpr (!LAST) {
@@ -643,7 +670,7 @@ __global__ void __launch_bounds__(512, 2) fwd_kernel(FwdArgs a) {
     if (tid == 0) s_item = items.resolve();
     __syncthreads();
   }
-  if (tid == 0) retire(a.hdr->fwd_counter, &a.hdr->fwd_done);
+  if (tid == 0) retire(a.counter, a.done);
 }
 
 // =====================================================================================
@@ -837,35 +864,41 @@ struct BwdArgs {
   void* dq; void* dk; void* dv;    // fp32, or bf16 in the GRAD_BF16 instances of the kernels
   unsigned char* ds;               // dS spill buffer (2 KB fragments), or NULL
   WsHeader* hdr; const DevPair* pairs; const BwdDep* deps; const BwdItem* items; const QItem* dq_items;
+  const uint32_t* q_seg; const uint32_t* kv_seg;   // member bounds per Q-buffer row / KV-buffer row (packed blocks only)
   int64_t t_q;
   int32_t n_q_heads, n_kv_heads;
   float scale, scale_log2;
 };
 
 // Iterator over the 32-row query steps of a backward item: rows, then the G query heads of
-// the group, then the dependent query blocks.  A DIAG dependency starts at the tile's own rows.
+// the group, then the dependent query blocks.  A DIAG (or PACKED_DIAG) dependency starts at the tile's own rows.
 struct StepIter {
   const BwdDep* deps;
-  int dep, n_deps, hh, group, q0, first_diag;
+  int dep, n_deps, hh, group, q0, first_diag, q_stop;   // q_stop: first row past the rows to walk in the current dependency
   BwdDep cur;
   bool more;
-  __device__ __forceinline__ int first_q0() const { return cur.kind == FCP_KIND_DIAG ? first_diag : 0; }
-  __device__ __forceinline__ void init(const BwdDep* d, int n, int group_, int tile_off) {
-    deps = d; dep = 0; n_deps = n; hh = 0; group = group_; first_diag = tile_off & ~31; q0 = 0;
+  __device__ __forceinline__ int first_q0() const { return (cur.kind & 1) ? first_diag : 0; }
+  // packed_q_end: of an item of a packed block (whose one dependency is walked up to that row only), else 0
+  __device__ __forceinline__ void init(const BwdDep* d, int n, int group_, int tile_off, int packed_q_end) {
+    deps = d; dep = 0; n_deps = n; hh = 0; group = group_; first_diag = tile_off & ~31; q0 = 0; q_stop = 0;
     cur = BwdDep{0, 0, 0, 0};
     more = n > 0;
-    if (more) { cur = deps[0]; q0 = first_q0(); }
+    if (more) {
+      cur = deps[0]; q0 = first_q0();
+      q_stop = packed_q_end > 0 ? packed_q_end : cur.q_len;
+      more = q0 < q_stop;
+    }
   }
   __device__ __forceinline__ void advance() {
     q0 += 32;
-    if (q0 >= cur.q_len) {
+    if (q0 >= q_stop) {
       hh++;
       if (hh < group) {
         q0 = first_q0();
       } else {
         hh = 0;
         dep++;
-        if (dep < n_deps) { cur = deps[dep]; q0 = first_q0(); } else { more = false; }
+        if (dep < n_deps) { cur = deps[dep]; q0 = first_q0(); q_stop = cur.q_len; } else { more = false; }
       }
     }
   }
@@ -889,6 +922,7 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds_t[NB][BUF];
   __shared__ __attribute__((aligned(1024))) unsigned char lds_h[2][4][4096];   // [parity][KV sub-tile][operand][lane] 16 B
   __shared__ __attribute__((aligned(256))) float lds_sc[NB][64];   // [LSE*log2e x 32 | D*scale x 32]
+  __shared__ int s_khi[256];        // packed block: first query row past the member of each producer lane's KV row, minus 4g
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -930,12 +964,13 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
     int n_iv = 2;       // barrier intervals of the item: its steps plus two of pipeline fill, rounded up to even
     for (int d = 0; d < it.n_deps; d++) {
       const BwdDep dd = a.deps[it.dep_begin + d];
-      const int first = dd.kind == FCP_KIND_DIAG ? (it.tile_off & ~31) : 0;
-      n_iv += group * ((dd.q_len - first + 31) / 32);
+      const int first = (dd.kind & 1) ? (it.tile_off & ~31) : 0;
+      const int stop = it.packed ? it.q_end : dd.q_len;
+      n_iv += group * (max(0, stop - first + 31) / 32);
     }
     n_iv = (n_iv + 1) & ~1;
     StepIter si;
-    si.init(a.deps + it.dep_begin, it.n_deps, group, it.tile_off);
+    si.init(a.deps + it.dep_begin, it.n_deps, group, it.tile_off, it.packed ? it.q_end : 0);
 
     if (consumer) {
       // =============================== consumer ===============================
@@ -1084,6 +1119,14 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
     } else {
       // =============================== producer ===============================
       int kvg = it.tile_off + my_kv - 4 * g;       // masked iff kvg > q0 + 8*(r/4) + r%4 on a DIAG step
+      if (it.packed) {
+        // Packed block: a KV row is seen by the query rows of its own member only, [first, last + 1) inside the
+        // block: kvg becomes that first row under a full mask (under a causal one it is the row itself, as
+        // above), and the bound past the last row waits in LDS for the masked intervals.
+        const uint32_t sg = kv_ok ? a.kv_seg[it.kv_start + my_kv] : 0u;
+        if (!(it.packed & 1)) kvg = (int)(sg & 0xffff) - 4 * g;
+        s_khi[tid] = (int)(sg >> 16) - 4 * g;
+      }
       // SPILL: the dS this wave forms also goes to memory, one 2 KB fragment per step, for the dQ pass.  There a
       // KV row past the ragged end of the tile must carry dS = 0 (here its column of dK^T / dV^T is simply never
       // stored): such lanes get a threshold nothing passes, and a ragged tile runs every step through the masked
@@ -1131,8 +1174,10 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 
       // One interval: MFMAs of A(i+2) into (sn, dpn); B(i+1) on (sc, dpc) between them.
       auto interval = [&](auto masked, f32x16& sc, f32x16& dpc, f32x16& sn, f32x16& dpn) {
-        constexpr bool MASK = decltype(masked)::value;
+        constexpr int MASK = decltype(masked)::value;     // 0: no mask, 1: diagonal / ragged end, 2: packed block
         const int thr_s = __builtin_amdgcn_readfirstlane(thr_t);
+        int hlim = 0;                                     // packed: rows 8*(r/4) + r%4 >= hlim of the step are past the member
+        if constexpr (MASK == 2) hlim = s_khi[tid] - thr_s;
         f32x4 lse_c = lse_n, dl_c = dl_n;      // scalars of rows 8*q4 + 4g .. +3, one group of four ahead
         uint32_t pk[16];           // [0..7] P pairs, [8..15] dS pairs: four B operands for the consumer
         float p_prev = 0.f, ds_prev = 0.f;
@@ -1184,7 +1229,8 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
               p_ahead = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r + 1], a.scale_log2, -lse_q));
             }
             const float dl_r = dl_c[r & 3];
-            if constexpr (MASK) p = (kvg > thr_s + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
+            if constexpr (MASK == 1) p = (kvg > thr_s + 8 * (r >> 2) + (r & 3)) ? 0.f : p;
+            if constexpr (MASK == 2) p = (kvg > thr_s + 8 * (r >> 2) + (r & 3) || 8 * (r >> 2) + (r & 3) >= hlim) ? 0.f : p;
             const float ds = p * __builtin_fmaf(dpc[r], a.scale, -dl_r);
             if (r & 1) {
               pk[r >> 1] = pack_bf16(p_prev, p); pk[8 + (r >> 1)] = pack_bf16(ds_prev, ds);
@@ -1214,12 +1260,12 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         thr_t = thr_none;
         if constexpr (SPILL) frag_t = sink;
         if (si.more) {
-          if (si.cur.kind == FCP_KIND_DIAG) thr_t = si.q0;
+          if (si.cur.kind != FCP_KIND_FULL) thr_t = si.q0;
           if constexpr (SPILL) {
             const int q32 = si.q0 >> 5, nq32 = (si.cur.q_len + 31) >> 5;
             const int head = it.kv_head * group + si.hh;
             if (sub * 32 < it.kv_rows) {
-              if (si.cur.kind == FCP_KIND_DIAG) {
+              if (si.cur.kind & 1) {
                 if (my_kv32 <= q32) frag_t = si.cur.ds_frag + head * (nq32 * (nq32 + 1) / 2) + q32 * (q32 + 1) / 2 + my_kv32;
               } else {
                 frag_t = si.cur.ds_frag + (head * nq32 + q32) * nkv32 + my_kv32;
@@ -1231,11 +1277,20 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
         hb ^= 1;
       };
       // the first interval handles B(-1) (nothing) and A(0), the second B(0) and A(1), ...
-      const std::true_type with_mask;
-      const std::false_type no_mask;
-      for (int iv = 0; iv < n_iv; iv += 2) {
-        if (thr_t != kNoMask) interval(with_mask, s_a, dp_a, s_b, dp_b); else interval(no_mask, s_a, dp_a, s_b, dp_b);
-        if (thr_t != kNoMask) interval(with_mask, s_b, dp_b, s_a, dp_a); else interval(no_mask, s_b, dp_b, s_a, dp_a);
+      const std::integral_constant<int, 0> no_mask;
+      const std::integral_constant<int, 1> with_mask;
+      const std::integral_constant<int, 2> packed_mask;
+      if (it.packed) {
+        // every step masked by member; outside the item's steps thr_t names no row at all, which masks everything
+        for (int iv = 0; iv < n_iv; iv += 2) {
+          interval(packed_mask, s_a, dp_a, s_b, dp_b);
+          interval(packed_mask, s_b, dp_b, s_a, dp_a);
+        }
+      } else {
+        for (int iv = 0; iv < n_iv; iv += 2) {
+          if (thr_t != kNoMask) interval(with_mask, s_a, dp_a, s_b, dp_b); else interval(no_mask, s_a, dp_a, s_b, dp_b);
+          if (thr_t != kNoMask) interval(with_mask, s_b, dp_b, s_a, dp_a); else interval(no_mask, s_b, dp_b, s_a, dp_a);
+        }
       }
     }
     __syncthreads();
@@ -1253,12 +1308,15 @@ __global__ void __launch_bounds__(512, 2) dkdv_kernel(BwdArgs a) {
 // Columns past the diagonal or past a ragged end get P = 0.  Every dQ row has one writer: plain
 // stores, deterministic.
 // =====================================================================================
-template <int D, bool WITH_D, bool GRAD_BF16>
+// PACKED: the problem has packed blocks; only that instance carries the per-row member bounds (as in the forward).
+// It exists without WITH_D only: on such a problem the launcher runs the stand-alone D pass first.
+template <int D, bool WITH_D, bool GRAD_BF16, bool PACKED = false>
 __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
   constexpr int KC = D / 16;
   constexpr int DT = D / 32;
   constexpr int TB = tile_bytes<D>(kFwdTileN);
   __shared__ __attribute__((aligned(1024))) unsigned char lds_kv[2][2 * TB];   // [buffer][K tile | V tile]
+  __shared__ uint32_t s_seg[512];   // member bounds of each lane's query row in a packed block (written and read by that lane)
   __shared__ int s_item;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -1305,6 +1363,9 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
     const int wave_row_lo = tile_off_q + wq * 32;
     const uint16_t* kbase = a.k + (int64_t)kvh * D;
     const uint16_t* vbase = a.v + (int64_t)kvh * D;
+    if constexpr (PACKED) {
+      if (it.col_end > 0) s_seg[tid] = row_ok ? a.q_seg[q_start + my_row] : 0u;   // packed block: visible columns of the row
+    }
 
     bf16x8 qf[KC], dof[KC];
     float lse_l = INFINITY, dl_l = 0.f;     // rows past the end: P = exp2(-inf) = 0
@@ -1384,7 +1445,7 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
       for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
 
     TileIter ti;
-    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
+    ti.init(a.pairs, it);
     auto dma = [&](int b) {
       const int64_t row0 = (int64_t)(ti.cur.kv_start + ti.c0) * kv_row_stride;
       // Only the waves of sub-item 0 load: they reach every tile barrier well before the others (the SIMD
@@ -1395,7 +1456,7 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
       }
     };
     DevPair tp = ti.cur;
-    int tc0 = 0;
+    int tc0 = ti.c0;       // not always 0: an item of a packed block starts at its own first column
     bool have = ti.more;
     if (have) { dma(buf); ti.advance(); }
     dma_wait();
@@ -1406,13 +1467,19 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
       const bool nhave = ti.more;
       if (nhave) { dma(buf ^ 1); ti.advance(); }
 
-      const bool diag = tp.kind == FCP_KIND_DIAG;
+      const bool diag = (tp.kind & 1) != 0, packed = PACKED && (tp.kind & 2) != 0;
       if (!(diag && tc0 > wave_row_lo + 31)) {      // else nothing visible for this wave
         // wave-uniform: tiles that straddle the diagonal, and tiles that hold a ragged end (their K rows past
         // the end are zero in LDS, but S = 0 there still gives P = exp2(-LSE), which overflows for a row whose
         // logits are all strongly negative; inf * 0 would then poison the whole dQ row)
-        const bool need_mask = (diag && tc0 + kFwdTileN - 1 > wave_row_lo) || tc0 + kFwdTileN > tp.kv_len;
-        const int limit = diag ? tile_off_q + my_row : tp.kv_len - 1;      // last visible column for this lane
+        const bool need_mask = packed || (diag && tc0 + kFwdTileN - 1 > wave_row_lo) || tc0 + kFwdTileN > tp.kv_len;
+        int limit = diag ? tile_off_q + my_row : tp.kv_len - 1;      // last visible column for this lane
+        int first = 0;                                               // first one (a packed block: the row's own member)
+        if (packed) {
+          const uint32_t sg = s_seg[tid];
+          first = (int)(sg & 0xffff);
+          limit = min(limit, (int)(sg >> 16) - 1);
+        }
         // the two 32-row halves of the KV tile one after the other: half the live accumulators
 #pragma unroll
         for (int rt = 0; rt < 2; rt++) {
@@ -1442,8 +1509,10 @@ __global__ void __launch_bounds__(512, 2) dq_kernel(BwdArgs a) {
           for (int r = 0; r < 16; r++) s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], a.scale_log2, -lse_l));
           if (need_mask) {                    // wave-uniform: only tiles that straddle the diagonal
 #pragma unroll
-            for (int r = 0; r < 16; r++)
-              if (tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3) > limit) s[r] = 0.f;
+            for (int r = 0; r < 16; r++) {
+              const int c = tc0 + rt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+              if (c > limit || c < first) s[r] = 0.f;
+            }
           }
 #pragma unroll
           for (int r = 0; r < 16; r++) s[r] *= __builtin_fmaf(dp[r], a.scale, -dl_l);
@@ -1589,7 +1658,7 @@ __global__ void __launch_bounds__(512, 2) dq_ds_kernel(BwdArgs a) {
       for (int r = 0; r < 16; r++) acc[dt][r] = 0.f;
 
     TileIter ti;
-    ti.init(a.pairs, it.pair_begin, it.n_pairs, max(it.tile_off[0] + it.q_rows[0], it.tile_off[1] + it.q_rows[1]));
+    ti.init(a.pairs, it);
     const int n_tiles = it.n_tiles;
     // The load of one tile: describe() = scalar bookkeeping, issue() = branch-free requests.
     uint64_t d_k = 0, d_ds = 0;
@@ -1605,14 +1674,14 @@ __global__ void __launch_bounds__(512, 2) dq_ds_kernel(BwdArgs a) {
         d_lim = (uint32_t)((valid - 1) * kv_row_stride * 2);
         const int f0 = ti.c0 >> 5;
         int frag;
-        if (ti.cur.kind == FCP_KIND_DIAG) {
+        if (ti.cur.kind & 1) {
           frag = ti.cur.ds_frag + head * (nq32 * (nq32 + 1) / 2) + q32 * (q32 + 1) / 2 + min(f0, q32);
         } else {
           const int nkv32 = (ti.cur.kv_len + 31) >> 5;
           frag = ti.cur.ds_frag + (head * nq32 + q32) * nkv32 + min(f0, nkv32 - 1);
         }
         d_ds = reinterpret_cast<uint64_t>(a.ds + (int64_t)frag * kDsFragBytes);
-        const int vis = ti.cur.kind == FCP_KIND_DIAG ? min(ti.cur.kv_len, wave_row_lo + 32) : ti.cur.kv_len;
+        const int vis = (ti.cur.kind & 1) ? min(ti.cur.kv_len, wave_row_lo + 32) : ti.cur.kv_len;
         d_vis = wave_ok ? max(0, min(kFwdTileN, vis - ti.c0)) : 0;
         ti.advance();
       }
@@ -1761,11 +1830,24 @@ static int launch_fwd(const char* who, const fcp_problem* p, const void* q, cons
   a.hdr = reinterpret_cast<WsHeader*>(ws);
   a.pairs = reinterpret_cast<const DevPair*>(ws + L.off_pairs);
   a.items = reinterpret_cast<const QItem*>(ws + L.off_fwd_items);
+  a.q_seg = reinterpret_cast<const uint32_t*>(ws + L.off_q_seg);
   a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.scale_log2 = resolve_scale(p) * kLog2e;
-  const int grid = (int)std::min<int64_t>(L.n_fwd_items, (int64_t)cu_count() * kFwdWgPerCu);
-  if (p->head_dim == 128) hipLaunchKernelGGL(fwd_kernel<128>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(fwd_kernel<64>, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  // two launches: the items of ordinary blocks, then (if any) those of packed blocks through the instance for them;
+  // they write different rows, and the stream keeps them in order
+  const int64_t n_plain = L.n_fwd_items - L.n_fwd_packed_items;
+  if (n_plain > 0) {
+    a.counter = a.hdr->fwd_counter; a.begin = a.hdr->fwd_begin; a.done = &a.hdr->fwd_done;
+    const int grid = (int)std::min<int64_t>(n_plain, (int64_t)cu_count() * kFwdWgPerCu);
+    if (p->head_dim == 128) hipLaunchKernelGGL((fwd_kernel<128, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((fwd_kernel<64, false>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  }
+  if (L.n_fwd_packed_items > 0) {
+    a.counter = a.hdr->fwdp_counter; a.begin = a.hdr->fwdp_begin; a.done = &a.hdr->fwdp_done;
+    const int grid = (int)std::min<int64_t>(L.n_fwd_packed_items, (int64_t)cu_count() * kFwdWgPerCu);
+    if (p->head_dim == 128) hipLaunchKernelGGL((fwd_kernel<128, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((fwd_kernel<64, true>), dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+  }
   return check_launch(who);
 }
 
@@ -1889,6 +1971,8 @@ static int fill_bwd_args(const fcp_problem* p, WsLayout* L, BwdArgs* a, void* wo
   a->deps = reinterpret_cast<const BwdDep*>(ws + L->off_bwd_deps);
   a->items = reinterpret_cast<const BwdItem*>(ws + L->off_bwd_items);
   a->dq_items = reinterpret_cast<const QItem*>(ws + L->off_dq_items);
+  a->q_seg = reinterpret_cast<const uint32_t*>(ws + L->off_q_seg);
+  a->kv_seg = reinterpret_cast<const uint32_t*>(ws + L->off_kv_seg);
   a->n_q_heads = p->n_q_heads; a->n_kv_heads = p->n_kv_heads;
   a->scale = resolve_scale(p); a->scale_log2 = a->scale * kLog2e;
   a->dq = nullptr; a->dk = nullptr; a->dv = nullptr;
@@ -1931,7 +2015,19 @@ static int launch_dq(const char* who, const fcp_problem* p, const void* q, const
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.dq = dq;
   const int grid = (int)std::min<int64_t>(L.n_dq_items, (int64_t)cu_count() * kDqWgPerCu);
-  const bool with_d = o != nullptr, gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0, d128 = p->head_dim == 128;
+  const bool gb = (p->flags & FCP_FLAG_GRAD_BF16) != 0, d128 = p->head_dim == 128, packed = p->n_segments > 0;
+  if (packed) {
+    // the kernel instance for packed blocks reads D and LSE from the workspace: run the D pass here if the caller has not
+    if (o) {
+      rc = fcp_bwd_preprocess(p, o, lse, d_o, workspace, stream);
+      if (rc) return rc;
+    }
+    void (*kern)(BwdArgs) = d128 ? (gb ? dq_kernel<128, false, true, true> : dq_kernel<128, false, false, true>)
+                                 : (gb ? dq_kernel<64, false, true, true> : dq_kernel<64, false, false, true>);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, (hipStream_t)stream, a);
+    return check_launch(who);
+  }
+  const bool with_d = o != nullptr;
   if (with_d) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     a.o = o; a.lse = lse; a.o_is_f32 = (p->flags & FCP_FLAG_O_F32) ? 1 : 0;

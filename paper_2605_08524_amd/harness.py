@@ -17,20 +17,64 @@ def to_dev_bf16(bits: np.ndarray, device) -> torch.Tensor:
     return t.view(torch.bfloat16)
 
 
-class DevicePath:
-    """Holds the device buffers of one workload and runs the path's calls on them."""
+def packed_plan(wl):
+    """The workload's plan with its short sequences packed into shared blocks: block costs -> scheduling units ->
+    fcp_plan_blocks_packed, all in the library's host code."""
+    blocks, mem, comp = B.fcp_block_costs(wl.seq_lens, wl.block_size, wl.causal)
+    unit_of_block = B.fcp_pack_units(blocks, mem, comp, wl.block_size)[0] if len(blocks) else None
+    return B.fcp_plan_blocks_packed(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned, unit_of_block)
 
-    def __init__(self, wl, device, flags=0, backward=False, stream=None, softmax_scale=0.0):
+
+def buffer_rows(wl, plan):
+    """Where the rows of a plan's buffers come from in the workload's tensors, which are sequence-major (K / V: all
+    tokens by sequence; Q / dO: the owned blocks by (seq, idx)).  Returns (kv_src, q_src), int64 index arrays; for a
+    plan without packed blocks both are the identity.  Pure table look-ups: the plan fixes the layout."""
+    bs = wl.block_size
+    seq_off = np.concatenate([[0], np.cumsum(np.asarray(wl.seq_lens, dtype=np.int64))])
+    flat = B.fcp_plan_blocks(wl.seq_lens, bs, wl.causal, 0, wl.q_owned)["q_blocks"]
+    q_home = {(int(s), int(i)): int(st) for s, i, st, _ in flat}          # (seq, idx) -> first row in the workload's Q
+    members = {}
+    for kb, s, off, ln in plan.get("segments", ()):
+        members.setdefault(int(kb), []).append((int(s), int(ln)))
+    kv_index = {(int(b[0]), int(b[1])): n for n, b in enumerate(plan["kv_blocks"])}
+    kv_src, q_src = [], []
+    for kb, (s, i, _, ln) in enumerate(plan["kv_blocks"]):
+        if kb in members:
+            kv_src += [seq_off[ms] + np.arange(mlen) for ms, mlen in members[kb]]
+        else:
+            kv_src.append(seq_off[s] + int(i) * bs + np.arange(ln))
+    for s, i, _, ln in plan["q_blocks"]:
+        kb = kv_index[(int(s), int(i))]
+        if kb in members:
+            q_src += [q_home[(ms, 0)] + np.arange(mlen) for ms, mlen in members[kb]]
+        else:
+            q_src.append(q_home[(int(s), int(i))] + np.arange(ln))
+    cat = lambda parts: np.concatenate(parts).astype(np.int64) if parts else np.zeros(0, dtype=np.int64)
+    return cat(kv_src), cat(q_src)
+
+
+class DevicePath:
+    """Holds the device buffers of one workload and runs the path's calls on them.  packed=True plans the workload
+    with fcp_plan_blocks_packed and lays the tensors out in that plan's order (kv_src / q_src say which row of the
+    workload's sequence-major tensors each buffer row holds)."""
+
+    def __init__(self, wl, device, flags=0, backward=False, stream=None, softmax_scale=0.0, packed=False):
         self.wl, self.device, self.stream = wl, device, stream
         t0 = time.perf_counter()
-        self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+        if packed:
+            self.plan = packed_plan(wl)
+        else:
+            self.plan = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
         self.plan_ms = (time.perf_counter() - t0) * 1e3              # host: block table, pair list, slots
         self.problem = B.Problem(self.plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, softmax_scale, flags)
         p = self.problem
         Hq, Hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
-        self.q = to_dev_bf16(wl.q(), device)
-        self.k = to_dev_bf16(wl.k(), device)
-        self.v = to_dev_bf16(wl.v(), device)
+        self.kv_src, self.q_src = buffer_rows(wl, self.plan) if packed else (None, None)
+        lay_q = (lambda x: x[self.q_src]) if packed else (lambda x: x)
+        lay_kv = (lambda x: x[self.kv_src]) if packed else (lambda x: x)
+        self.q = to_dev_bf16(lay_q(wl.q()), device)
+        self.k = to_dev_bf16(lay_kv(wl.k()), device)
+        self.v = to_dev_bf16(lay_kv(wl.v()), device)
         f32 = dict(dtype=torch.float32, device=device)
         nan = float("nan")
         part_dtype = torch.bfloat16 if (flags & B.FCP_FLAG_PART_BF16) else torch.float32
@@ -49,7 +93,7 @@ class DevicePath:
         B.fcp_queue_build(p, self.ws_ptr, self.ws_bytes, stream)
         self.queue_build_ms = (time.perf_counter() - t0) * 1e3     # host: work items + one upload (returns when it is done)
         if backward:
-            self.d_o = to_dev_bf16(wl.d_o(), device)
+            self.d_o = to_dev_bf16(lay_q(wl.d_o()), device)
             g_dtype = torch.bfloat16 if (flags & B.FCP_FLAG_GRAD_BF16) else torch.float32
             self.dq = torch.full((max(1, p.t_q), Hq, d), nan, dtype=g_dtype, device=device)
             self.dk = torch.full((max(1, p.t_kv), Hkv, d), nan, dtype=g_dtype, device=device)
@@ -89,9 +133,9 @@ class DevicePath:
                                 self.dq, self.ws_ptr, self.stream)
 
 
-def run_path(wl, device, backward=False, flags=0, softmax_scale=0.0):
-    """One pass of the whole path; returns host copies (numpy) of every output."""
-    dp = DevicePath(wl, device, flags=flags, backward=backward, softmax_scale=softmax_scale)
+def run_path(wl, device, backward=False, flags=0, softmax_scale=0.0, packed=False):
+    """One pass of the whole path; returns host copies (numpy) of every output, in the layout of the plan's buffers."""
+    dp = DevicePath(wl, device, flags=flags, backward=backward, softmax_scale=softmax_scale, packed=packed)
     dp.fwd()
     dp.merge()
     if backward:

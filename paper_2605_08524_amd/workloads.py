@@ -184,6 +184,19 @@ def make_workload(config: int, seed: int = 0) -> Workload:
     raise ValueError(f"unknown config {config}")
 
 
+def short_mix_workload(seed: int = 0, total: int = 65536, lo: int = 16, hi: int = 256, block_size: int = 1024) -> Workload:
+    """A batch of short sequences only (lengths uniform in [lo, hi), all shorter than a block), the case the paper's
+    sharding policy packs into shared blocks; model shape of the training configuration."""
+    rng = np.random.default_rng([int(seed), 3])
+    lens, acc = [], 0
+    while acc < total:
+        L = min(int(rng.integers(lo, hi)), total - acc)
+        lens.append(L)
+        acc += L
+    return Workload("short-mix", seed, np.asarray(lens, dtype=np.int32), int(block_size), 1, 16, 32, 8, 128,
+                    notes=f"{total} tokens of sequences uniform[{lo},{hi}); GQA 32/8 d=128")
+
+
 def custom_workload(seq_lens, block_size, causal=1, coalesce=0, n_q_heads=4, n_kv_heads=4,
                     head_dim=64, q_owned=None, seed=0, name="custom") -> Workload:
     return Workload(name, seed, np.asarray(seq_lens, dtype=np.int32), int(block_size), int(causal),

@@ -150,14 +150,14 @@ DIRECT = 2   # FCP_FLAG_DIRECT_SINGLE
 SPILL = 16   # FCP_FLAG_BWD_SPILL_DS
 
 
-def _run(wl, backward, flags, timed=True):
+def _run(wl, backward, flags, timed=True, packed=False):
     dev = torch.device("cuda:0")
     t0 = time.time()
     if timed:
         flags |= DIRECT
     if timed is True and backward:
         flags |= SPILL
-    dp = DevicePath(wl, dev, flags=flags, backward=backward)
+    dp = DevicePath(wl, dev, flags=flags, backward=backward, packed=packed)
     _say(f"  inputs generated and uploaded in {time.time() - t0:.1f} s; "
          f"{len(dp.plan['pairs'])} pairs, {len(dp.plan['slots'])} slots, {dp.problem.n_slot_rows} partial rows")
     dp.fwd()
@@ -359,6 +359,44 @@ def test_config4_multimodal_mix_sampled():
     pos = list(rng.choice(owned_pos, size=16, replace=False)) + [int(owned_pos[0]), int(owned_pos[-1])]
     _rows_check(wl, host, long_seq, pos, accs, False, koff, qrow)
     accs["o"].check()
+    accs["lse"].check(TOL_LSE, None)
+
+
+@pytest.mark.timeout(900)
+def test_config4_multimodal_mix_packed_blocks():
+    """Config 4 planned with fcp_plan_blocks_packed (block costs -> scheduling units -> packed plan, all in the library):
+    tables against the oracle's chain, then forward and backward on the timed launches; every member of a packed block
+    is checked whole (O, LSE, dQ, dK, dV), with some unpacked short sequences and sampled rows of the long one."""
+    from oracle import fcp_sched_oracle as sch
+    wl = workloads.make_workload(4, 0)
+    _say(f"case {wl.name} packed: {len(wl.seq_lens)} sequences, long one {int(wl.seq_lens[-1])} tokens")
+    got, plan = _run(wl, True, F32, packed=True)
+    flat = orc.plan_blocks(wl.seq_lens, wl.block_size, wl.causal, 0)["kv_blocks"]
+    unit, _, _ = sch.pack_units(flat, [int(b[3]) for b in flat], [0] * len(flat), wl.block_size)
+    ref = orc.plan_blocks_packed(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned, unit)
+    for key in ("kv_blocks", "q_blocks", "pairs", "slots", "segments"):
+        assert np.array_equal(ref[key], plan[key]), key
+    members = sorted(set(int(s) for _, s, _, _ in ref["segments"]))
+    assert len(members) >= 20
+    # back to the sequence-major layout that the sampling helpers index
+    kv_src, q_src = orc.packed_row_maps(ref, wl.seq_lens, wl.block_size, wl.q_owned)
+    host = {}
+    for name, src in (("o", q_src), ("lse", q_src), ("dq", q_src), ("dk", kv_src), ("dv", kv_src)):
+        assert np.all(np.isfinite(got[name]) | (np.isneginf(got[name]) if name == "lse" else False)), name
+        host[name] = np.empty_like(got[name])
+        host[name][src] = got[name]
+    koff, qrow = _seq_geometry(wl)
+    accs = {n: _Acc(n) for n in ("o", "lse", "dq", "dk", "dv")}
+    rng = np.random.default_rng(6)
+    others = [int(s) for s in rng.permutation(len(wl.seq_lens) - 1) if int(s) not in members][:6]
+    for s in members + others:
+        _whole_seq_check(wl, host, s, accs, True, koff, qrow)
+    long_seq = len(wl.seq_lens) - 1
+    owned_pos = np.nonzero(qrow[long_seq] >= 0)[0]
+    pos = list(rng.choice(owned_pos, size=8, replace=False)) + [int(owned_pos[0]), int(owned_pos[-1])]
+    _rows_check(wl, host, long_seq, pos, accs, True, koff, qrow)
+    for n in ("o", "dq", "dk", "dv"):
+        accs[n].check()
     accs["lse"].check(TOL_LSE, None)
 
 

@@ -545,3 +545,72 @@ def test_running_merge_rejects_several_slots_per_block():
     with pytest.raises(fcp.FcpError) as e:
         dp_fwd = fcp.fcp_block_attn_fwd_out(dp.problem, dp.q, dp.k, dp.v, None, None, dp.o, dp.lse, dp.ws_ptr, None)
     assert e.value.code == fcp.binding.FCP_ERR_INVALID_ARG
+
+
+# ---- packed blocks: the short sequences of a scheduling unit as ONE block for the kernels ---------------------
+PACKED = [
+    # seq_lens, block, causal, c, Hq, Hkv, d, owned
+    ([60, 40, 28], 128, 1, 0, 4, 2, 64, None),                      # one packed block, exactly full
+    ([100, 156, 30, 70, 90], 256, 1, 2, 4, 2, 128, None),           # two packed blocks, members straddling row tiles
+    ([64, 64, 64, 64, 300, 17], 256, 1, 1, 8, 2, 128, None),        # members on tile boundaries, beside a long sequence
+    ([33, 1, 200, 95, 700, 5, 129], 256, 0, 2, 4, 4, 64, None),     # non-causal
+    ([500, 120, 3000, 77, 250, 64, 900], 512, 1, 4, 4, 1, 128, None),   # several tiles per packed block
+    ([90, 30, 1300, 60, 50], 128, 1, 4, 6, 2, 64, [(0, 0), (1, 0), (2, 3), (2, 10)]),   # a share: unit (0, 1) owned, unit (3, 4) not; odd group
+    ([31, 33], 64, 1, 0, 2, 2, 128, None),
+]
+
+
+def _packed_parity(wl, flags, backward=True):
+    from oracle import fcp_sched_oracle as sch
+    _say(f"case {wl.name} seed={wl.seed} lens={list(wl.seq_lens)[:8]}.. bs={wl.block_size} c={wl.coalesce} causal={wl.causal} "
+         f"H={wl.n_q_heads}/{wl.n_kv_heads} d={wl.head_dim} flags={flags}")
+    res = run_path(wl, torch.device("cuda:0"), backward=backward, flags=flags, packed=True)
+    # tables: the oracle's own block costs -> units -> packed plan
+    flat = orc.plan_blocks(wl.seq_lens, wl.block_size, wl.causal, 0)["kv_blocks"]
+    unit, _, _ = sch.pack_units(flat, [int(b[3]) for b in flat], [0] * len(flat), wl.block_size)
+    plan = orc.plan_blocks_packed(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned, unit)
+    for key in ("kv_blocks", "q_blocks", "pairs", "slots", "segments"):
+        assert np.array_equal(plan[key], res["plan"][key]), key
+    assert len(plan["segments"]) > 0
+    kv_src, q_src = orc.packed_row_maps(plan, wl.seq_lens, wl.block_size, wl.q_owned)
+    q, k, v = wl.q(), wl.k(), wl.v()
+    o_ref, lse_ref = orc.worker_fwd(q, k, v, wl.seq_lens, wl.block_size, wl.causal, wl.q_owned)
+    _check("o", res["o"], o_ref[q_src])
+    _check_lse("lse", res["lse"], lse_ref[q_src])
+    if backward:
+        dq, dk, dv = orc.worker_bwd(q, k, v, wl.d_o(), wl.seq_lens, wl.block_size, wl.causal, wl.q_owned)
+        _check("dq", res["dq"], dq[q_src])
+        _check("dk", res["dk"], dk[kv_src])
+        _check("dv", res["dv"], dv[kv_src])
+    return res, plan
+
+
+@pytest.mark.parametrize("case", range(len(PACKED)))
+@pytest.mark.parametrize("flags", [F32, F32 | 16, F32 | 2 | 16])
+def test_packed_blocks_fwd_bwd(case, flags):
+    """Forward, merge and both backward variants (recomputing; dS kept in the workspace) on plans whose short sequences
+    share blocks, against the per-sequence oracle with its rows moved to the plan's layout."""
+    lens, bs, causal, c, hq, hkv, d, owned = PACKED[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=300 + case, name=f"packed{case}")
+    _packed_parity(wl, flags)
+
+
+def test_packed_blocks_cut_work_items_and_tiles():
+    """Packing must shrink what the kernels are given: fewer query blocks, hence fewer forward work items."""
+    from paper_2605_08524_amd import binding as B
+    from paper_2605_08524_amd.harness import packed_plan
+    wl = workloads.custom_workload([100, 156, 30, 70, 90, 64, 64, 64], 256, 1, 0, 4, 2, 128, seed=1, name="packed-count")
+    plain = B.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce)
+    packed = packed_plan(wl)
+    assert len(packed["q_blocks"]) < len(plain["q_blocks"]) and len(packed["pairs"]) < len(plain["pairs"])
+    _packed_parity(wl, F32, backward=False)
+
+
+def test_packed_config4_sample():
+    """The multimodal mix (90 % short sequences beside the tail of a long one), reduced in length so that the oracle
+    finishes: packed plan, forward and backward with dS kept."""
+    rng = np.random.default_rng(4)
+    lens = [int(x) for x in rng.integers(16, 400, size=40)] + [3000]
+    owned = [(s, i) for s, L in enumerate(lens[:-1]) for i in range(-(-L // 256))] + [(len(lens) - 1, i) for i in (9, 10, 11)]
+    wl = workloads.custom_workload(lens, 256, 1, 16, 4, 4, 128, q_owned=owned, seed=44, name="packed-multimodal")
+    _packed_parity(wl, F32 | 2 | 16)

@@ -196,3 +196,75 @@ def test_stage_tables_errors():
     with pytest.raises(fcp.FcpError) as e:
         fcp.fcp_stage_tables(bad, 0)
     assert e.value.code == binding.FCP_ERR_INVALID_ARG
+
+
+def _units(seq_lens, bs, causal):
+    from oracle import fcp_sched_oracle as sch
+    flat = orc.plan_blocks(seq_lens, bs, causal, 0)["kv_blocks"]
+    return sch.pack_units(flat, [int(b[3]) for b in flat], [0] * len(flat), bs)[0] if len(flat) else None
+
+
+def test_packed_plan_matches_oracle_random():
+    """fcp_plan_blocks_packed against the oracle's packed planner, bit for bit, on random batches and shares."""
+    rng = np.random.default_rng(11)
+    for trial in range(150):
+        bs = int(rng.choice([4, 8, 16]))
+        sl = rng.integers(0, 3 * bs, size=int(rng.integers(1, 12)))
+        causal, c = int(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 3]))
+        unit = _units(sl, bs, causal)
+        qo = None
+        if unit is not None and rng.random() < 0.5:
+            flat = orc.plan_blocks(sl, bs, causal, 0)["kv_blocks"]
+            keep = {u for u in set(unit) if rng.random() < 0.6}
+            qo = np.asarray([(int(flat[b][0]), int(flat[b][1])) for b in range(len(flat)) if unit[b] in keep], dtype=np.int32).reshape(-1, 2)
+        want = orc.plan_blocks_packed(sl, bs, causal, c, qo, unit)
+        got = fcp.fcp_plan_blocks_packed(sl, bs, causal, c, qo, unit)
+        for key in ("kv_blocks", "q_blocks", "pairs", "slots", "segments"):
+            assert np.array_equal(want[key], got[key]), (trial, key)
+        assert want["n_slot_rows"] == got["n_slot_rows"]
+
+
+def test_packed_plan_on_the_multimodal_config():
+    """Config 4 through block costs -> scheduling units -> packed plan, all in the library, against the same chain
+    in the oracles; the packed plan has fewer query blocks and pairs than the plain one."""
+    from paper_2605_08524_amd.harness import packed_plan
+    wl = workloads.make_workload(4, 0)
+    got = packed_plan(wl)
+    want = orc.plan_blocks_packed(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned,
+                                  _units(wl.seq_lens, wl.block_size, wl.causal))
+    for key in ("kv_blocks", "q_blocks", "pairs", "slots", "segments"):
+        assert np.array_equal(want[key], got[key]), key
+    plain = fcp.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+    assert len(got["q_blocks"]) < len(plain["q_blocks"]) and len(got["segments"]) > 0
+    assert orc.pair_nnz(want) == orc.pair_nnz(orc.plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned))
+    prob = fcp.Problem(got, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size)
+    assert fcp.fcp_workspace_bytes(prob) > 0
+
+
+def test_packed_plan_error_codes():
+    def code(*a):
+        with pytest.raises(fcp.FcpError) as e:
+            fcp.fcp_plan_blocks_packed(*a)
+        return e.value.code
+    assert code([10, 2], 4, 1, 0, None, [0, 1, 2, 2]) == -1          # a block of a long sequence shares a unit
+    assert code([3, 3], 4, 1, 0, None, [0, 0]) == -1                 # the unit does not fit into a block
+    assert code([2, 1, 5], 4, 1, 0, [(0, 0), (2, 0)], [0, 0, 1, 2]) == -1   # a unit owned in part
+    assert code([2, 1], 4, 1, 0, None, [0, 7]) == -1                 # unit index out of range
+    assert code([2, 1], 4, 1, 0, None, None) == -1                   # blocks but no unit table
+
+
+def test_segment_tables_are_validated():
+    plan = fcp.fcp_plan_blocks_packed([3, 2, 9], 8, 1, 0, None, [0, 0, 1, 2])
+    assert plan["segments"].tolist() == [[0, 0, 0, 3], [0, 1, 3, 2]] and plan["pairs"][0].tolist() == [0, 0, 3, 0]
+
+    def rc(mutate):
+        bad = {k: (v.copy() if hasattr(v, "copy") else v) for k, v in plan.items()}
+        mutate(bad)
+        with pytest.raises(fcp.FcpError) as e:
+            fcp.fcp_workspace_bytes(fcp.Problem(bad, 2, 2, 64, 8))
+        return e.value.code
+    assert rc(lambda p: p["segments"].__setitem__((1, 3), 1)) == -1      # the members do not cover their block
+    assert rc(lambda p: p["segments"].__setitem__((1, 2), 2)) == -1      # a gap between members
+    assert rc(lambda p: p["pairs"].__setitem__((0, 2), 1)) == -1         # a DIAG pair on a block with members
+    assert rc(lambda p: p["pairs"].__setitem__((1, 2), 3)) == -1         # a PACKED pair on a block without members
+    assert rc(lambda p: p.__setitem__("segments", p["segments"][::-1].copy())) == -1   # not in (kv_blk, tok_off) order
