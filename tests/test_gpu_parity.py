@@ -614,3 +614,53 @@ def test_packed_config4_sample():
     owned = [(s, i) for s, L in enumerate(lens[:-1]) for i in range(-(-L // 256))] + [(len(lens) - 1, i) for i in (9, 10, 11)]
     wl = workloads.custom_workload(lens, 256, 1, 16, 4, 4, 128, q_owned=owned, seed=44, name="packed-multimodal")
     _packed_parity(wl, F32 | 2 | 16)
+
+
+@pytest.mark.parametrize("case", [1, 3, 4])
+def test_packed_blocks_through_the_other_entry_points(case):
+    """A packed plan through the allocation-free forward, the running merge (one launch per stage of the packed plan) and
+    the bf16-gradient backward: the forwards agree bit for bit with fcp_block_attn_fwd resp. to 1e-5 with the one-pass
+    merge, the bf16 gradients are the fp32 ones rounded once."""
+    import paper_2605_08524_amd as fcp
+    from paper_2605_08524_amd.harness import DevicePath
+    lens, bs, causal, c, hq, hkv, d, owned = PACKED[case]
+    wl = workloads.custom_workload(lens, bs, causal, c, hq, hkv, d, q_owned=owned, seed=300 + case, name=f"packed{case}-entries")
+    _say(f"case {wl.name}")
+    dev = torch.device("cuda:0")
+    res, plan = _packed_parity(wl, F32)
+    # allocation-free forward: same partials, bit for bit
+    dp = DevicePath(wl, dev, flags=0, backward=False, packed=True)
+    dp.fwd()
+    torch.cuda.synchronize(dev)
+    want_o, want_l = dp.o_part.clone(), dp.lse_part.clone()
+    dp.o_part.fill_(float("nan")); dp.lse_part.fill_(float("nan"))
+    fcp.fcp_block_attn_fwd_static(dp.problem, dp.q, dp.k, dp.v, dp.o_part, dp.lse_part, None)
+    torch.cuda.synchronize(dev)
+    n = dp.problem.n_slot_rows
+    assert torch.equal(want_o[:n], dp.o_part[:n]) and torch.equal(want_l[:n], dp.lse_part[:n])
+    # running merge over the stages of the packed plan
+    o = torch.full_like(dp.o, float("nan"), dtype=torch.float32)
+    lse = torch.full_like(dp.lse, float("-inf"))
+    _, n_stages = fcp.fcp_stage_tables(dp.plan, 0)
+    keep = []
+    for st in range(n_stages):
+        sp, _ = fcp.fcp_stage_tables(dp.plan, st)
+        prob = fcp.Problem(sp, hq, hkv, d, bs, 0.0, fcp.FCP_FLAG_RUNNING_MERGE | fcp.FCP_FLAG_O_F32)
+        nbytes = fcp.fcp_workspace_bytes(prob)
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        ws_ptr = ws.data_ptr() + (-ws.data_ptr()) % 256
+        fcp.fcp_queue_build(prob, ws_ptr, nbytes, None)
+        fcp.fcp_block_attn_fwd_out(prob, dp.q, dp.k, dp.v, None, None, o, lse, ws_ptr, None)
+        keep.append((prob, ws))
+    torch.cuda.synchronize(dev)
+    t_q = dp.problem.t_q
+    err = float(np.max(np.abs(o[:t_q].cpu().numpy() - res["o"])))
+    _say(f"  running merge vs one-pass: max-abs {err:.3e} over {n_stages} stages")
+    assert err <= 1e-5
+    assert float(np.max(np.abs(lse[:t_q].cpu().numpy() - res["lse"]))) <= 1e-5
+    # bf16 gradients
+    b = run_path(wl, dev, backward=True, flags=F32 | 8 | 16, packed=True)
+    a = run_path(wl, dev, backward=True, flags=F32 | 16, packed=True)
+    for name in ("dq", "dk", "dv"):
+        want = torch.from_numpy(a[name]).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(want, b[name]), name
