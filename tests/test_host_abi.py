@@ -268,3 +268,37 @@ def test_segment_tables_are_validated():
     assert rc(lambda p: p["pairs"].__setitem__((0, 2), 1)) == -1         # a DIAG pair on a block with members
     assert rc(lambda p: p["pairs"].__setitem__((1, 2), 3)) == -1         # a PACKED pair on a block without members
     assert rc(lambda p: p.__setitem__("segments", p["segments"][::-1].copy())) == -1   # not in (kv_blk, tok_off) order
+
+
+def test_packed_block_size_limit():
+    """The kernels keep a token's member bounds in two 16-bit halves: a packed block above 65 535 tokens is refused
+    when the problem is validated (the planner itself has no such limit)."""
+    plan = fcp.fcp_plan_blocks_packed([40000, 29000], 70000, 1, 0, None, [0, 0])
+    assert plan["kv_blocks"].tolist() == [[0, 0, 0, 69000]] and len(plan["segments"]) == 2
+    with pytest.raises(fcp.FcpError) as e:
+        fcp.fcp_workspace_bytes(fcp.Problem(plan, 2, 2, 64, 70000))
+    assert e.value.code == -3
+    ok = fcp.fcp_plan_blocks_packed([40000, 25000], 70000, 1, 0, None, [0, 0])
+    assert fcp.fcp_workspace_bytes(fcp.Problem(ok, 2, 2, 64, 70000)) > 0
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_queue_tables_are_built_on_the_host_before_any_gpu_call(packed):
+    """Without a GPU, fcp_queue_build still validates the problem, lays out the workspace and builds every table (work
+    items, dependency lists, member bounds of packed blocks) in host memory; only the upload fails, with FCP_ERR_HIP.
+    This is how the queue builder runs under the host sanitizers."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("needs a box without a GPU: here the upload would be attempted")
+    from paper_2605_08524_amd.harness import packed_plan
+    cases = [workloads.custom_workload([100, 156, 30, 70, 90, 700, 17], 256, 1, 2, 6, 2, 128, seed=1),
+             workloads.custom_workload([33, 1, 200, 95, 700, 5, 129], 256, 0, 2, 4, 4, 64, seed=2),
+             workloads.make_workload(4, 0)]
+    for wl in cases:
+        plan = packed_plan(wl) if packed else fcp.fcp_plan_blocks(wl.seq_lens, wl.block_size, wl.causal, wl.coalesce, wl.q_owned)
+        for flags in (0, fcp.FCP_FLAG_DIRECT_SINGLE | fcp.FCP_FLAG_O_F32 | fcp.FCP_FLAG_BWD_SPILL_DS):
+            prob = fcp.Problem(plan, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block_size, 0.0, flags)
+            nbytes = fcp.fcp_workspace_bytes(prob)
+            with pytest.raises(fcp.FcpError) as e:
+                fcp.fcp_queue_build(prob, 4096, nbytes)      # an aligned address that is never written: the upload cannot start
+            assert e.value.code == -4, fcp.fcp_last_error()
