@@ -454,7 +454,14 @@ def probes(args):
             print(json.dumps({"probe": "mfma stream with vector work", "operands": kname, "fp32_fma_per_mfma": valu, "ms": round(ms, 3),
                               "mfma_tflops": round(tf, 1), "relative_to_no_vector_work": round(tf / base, 3),
                               "board_w": w and round(w), "sclk_mhz": mhz and round(mhz)}), flush=True)
-    src = torch.zeros(65536, dtype=torch.uint8, device=dev)
+    idle_w = None
+    if sampling:
+        ps.label = "idle"
+        time.sleep(1.0)
+        ps.label = None
+        idle_w, _ = ps.mean("idle")
+    # random bytes: what an access costs in energy depends on how many bits toggle
+    src = torch.randint(0, 256, (65536,), dtype=torch.uint8, device=dev)
     names = {0: ("ds_read_b128, swizzled rows", 1024), 1: ("ds_read_b64_tr_b16", 512), 2: ("ds_write_b128", 1024), 3: ("ds_write_b64", 512),
              4: ("LDS-DMA global_load_lds_dwordx4 (source in L2)", 1024)}
     for mode, (name, nbytes) in names.items():
@@ -463,9 +470,12 @@ def probes(args):
             ms, w, mhz = timed(f"lds {mode} {waves}", lambda: fcp_lds_probe(mode, waves, iters, src, out, stream))
             per_cu = waves * iters * 16.0 * nbytes
             line = {"probe": "lds throughput per compute unit", "access": name, "waves": waves, "ms": round(ms, 3),
-                    "bytes_per_ns": round(per_cu / ms / 1e6, 1), "sclk_mhz": mhz and round(mhz)}
+                    "bytes_per_ns": round(per_cu / ms / 1e6, 1), "sclk_mhz": mhz and round(mhz), "board_w": w and round(w)}
             if mhz:
                 line["bytes_per_clk"] = round(per_cu / ms / 1e6 / (mhz / 1e3), 1)
+            if w and idle_w:
+                # whole-chip rate: every compute unit runs the same loop
+                line["pj_per_byte_above_idle"] = round((w - idle_w) / (per_cu * n_cu / (ms * 1e-3)) * 1e12, 2)
             print(json.dumps(line), flush=True)
     n_rows, stride = 65536, 4096                 # 1 GiB of fp32: rows of 32 heads x 128
     buf = torch.zeros(n_rows * stride, dtype=torch.float32, device=dev)
