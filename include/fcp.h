@@ -249,7 +249,7 @@ int fcp_block_attn_fwd_out(const fcp_problem* p, const void* q, const void* k, c
  * which every device the library runs on holds until the process ends.  The call allocates no device
  * memory (no hipMalloc / hipFree, no allocating library routine); it waits on `stream` for its table
  * copy, then enqueues the kernel and returns.
- * Limits and errors: FCP_ERR_BUFFER_TOO_SMALL if the tables need more than 2 MiB (about 30 000 forward
+ * Limits and errors: FCP_ERR_BUFFER_TOO_SMALL if the tables need more than 2 MiB (about 25 000 forward
  * work items: the packed 64K-token training batch fits, the 1M-token share does not);
  * FCP_ERR_INVALID_ARG with FCP_FLAG_DIRECT_SINGLE (every slot goes to the partial buffers here);
  * otherwise as fcp_block_attn_fwd.  All calls on one device share that device's array, counters
