@@ -687,73 +687,89 @@ template <int D>
 __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
   constexpr int LPE = D / 4;            // lanes per entry
   constexpr int EPP = 256 / LPE;        // entries per pass
-  constexpr int U = 4;                  // entries in flight per thread (independent loads)
+  constexpr int U = 4;                  // entries per thread and step (independent loads; 2, 6 and 8 measured slower)
+  constexpr int STEP = EPP * U;         // entries the workgroup handles per step
   const MergeItem it = a.items[blockIdx.x];
   const int sub = threadIdx.x / LPE, ln = threadIdx.x % LPE;
-  for (int e0 = sub; e0 < it.n_rh; e0 += EPP * U) {
-    // One pass over the slots with a running maximum (the same recurrence as the online softmax):
-    // acc and tot are kept relative to mx and rescaled when a larger LSE arrives.  The loads of
-    // slot s+1 are in flight while slot s is folded in.
-    float mx[U], tot[U];
-    f32x4 acc[U];
-    bool ok[U];
+  // The item is one stream of steps (chunk of STEP entries, slot), slots innermost; the loads of a step are issued two
+  // steps before they are used, across chunk boundaries too, so that a query block with few partials keeps as many
+  // bytes in flight as one with many.  acc and tot are kept relative to a running maximum (the online-softmax
+  // recurrence) and rescaled when a larger LSE arrives.
+  const int n_chunks = (it.n_rh + STEP - 1) / STEP;
+  const int ns = max(it.n_slots, 1);    // a query block without any partial still gets O = 0, LSE = -inf: one empty step per chunk
+  const int n_steps = n_chunks * ns;
+  struct Buf { float l[U]; f32x4 x[U]; };
+  auto load = [&](int t, Buf& bf) {
+#pragma unroll
+    for (int u = 0; u < U; u++) { bf.l[u] = -INFINITY; bf.x[u] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    if (t >= n_steps || it.n_slots == 0) return;
+    const int c = t / ns, s = t - c * ns;
+    const int e0 = c * STEP + sub;
+    const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      ok[u] = e0 + u * EPP < it.n_rh;
-      mx[u] = -INFINITY; tot[u] = 0.f;
-      acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    float l[U], ln_[U];
-    f32x4 x[U], xn[U];
-    auto load = [&](int s, float (&ll)[U], f32x4 (&xx)[U]) {
-      const int64_t base = (int64_t)a.slot_rh[it.slot_begin + s] + it.rh_off + e0;
-#pragma unroll
-      for (int u = 0; u < U; u++) {
-        ll[u] = -INFINITY;
-        xx[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ok[u]) {
-          ll[u] = a.lse_part[base + u * EPP];
-          if (a.part_is_bf16) {
-            const u32x2 h = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.o_part) + (base + u * EPP) * D + ln * 4);
-            xx[u] = f32x4{__builtin_bit_cast(float, h[0] << 16), __builtin_bit_cast(float, h[0] & 0xffff0000u),
+      if (e0 + u * EPP < it.n_rh) {
+        bf.l[u] = a.lse_part[base + u * EPP];
+        if (a.part_is_bf16) {
+          const u32x2 h = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.o_part) + (base + u * EPP) * D + ln * 4));
+          bf.x[u] = f32x4{__builtin_bit_cast(float, h[0] << 16), __builtin_bit_cast(float, h[0] & 0xffff0000u),
                           __builtin_bit_cast(float, h[1] << 16), __builtin_bit_cast(float, h[1] & 0xffff0000u)};
-          } else {
-            xx[u] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.o_part) + (base + u * EPP) * D + ln * 4);
-          }
+        } else {
+          bf.x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.o_part) + (base + u * EPP) * D + ln * 4));
         }
       }
-    };
-    if (it.n_slots > 0) load(0, l, x);
-    for (int s = 0; s < it.n_slots; s++) {
-      if (s + 1 < it.n_slots) load(s + 1, ln_, xn);
+    }
+  };
+  float mx[U], tot[U];
+  f32x4 acc[U];
+  int s_in_chunk = 0, chunk = 0;
+  auto fold = [&](const Buf& bf) {
+    if (s_in_chunk == 0) {
 #pragma unroll
-      for (int u = 0; u < U; u++) {
-        // an empty partial (LSE = -inf) carries weight 0; its payload must not leak through (0 * NaN)
-        if (l[u] != -INFINITY) {
-          const float m_new = fmaxf(mx[u], l[u]);
-          const float keep = __expf(mx[u] - m_new);        // mx = -inf -> 0
-          const float w = __expf(l[u] - m_new);
-          tot[u] = tot[u] * keep + w;
-          acc[u] = acc[u] * keep + w * x[u];
-          mx[u] = m_new;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; u++) { l[u] = ln_[u]; x[u] = xn[u]; }
+      for (int u = 0; u < U; u++) { mx[u] = -INFINITY; tot[u] = 0.f; acc[u] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      if (!ok[u]) continue;
-      const float inv = tot[u] > 0.f ? 1.0f / tot[u] : 0.f;
-      const f32x4 r = acc[u] * inv;
-      const int64_t out = (int64_t)it.out_rh + e0 + u * EPP;
-      if (a.o_is_f32) {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.o) + out * D + ln * 4) = r;
-      } else {
-        u32x2 h = {pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3])};
-        *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.o) + out * D + ln * 4) = h;
+      // an empty partial (LSE = -inf) carries weight 0; its payload must not leak through (0 * NaN)
+      if (bf.l[u] != -INFINITY) {
+        const float m_new = fmaxf(mx[u], bf.l[u]);
+        const float keep = __expf(mx[u] - m_new);        // mx = -inf -> 0
+        const float w = __expf(bf.l[u] - m_new);
+        tot[u] = tot[u] * keep + w;
+        acc[u] = acc[u] * keep + w * bf.x[u];
+        mx[u] = m_new;
       }
-      if (ln == 0) a.lse[out] = tot[u] > 0.f ? mx[u] + __logf(tot[u]) : -INFINITY;
+    }
+    if (++s_in_chunk == ns) {
+      const int e0 = chunk * STEP + sub;
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (e0 + u * EPP >= it.n_rh) continue;
+        const float inv = tot[u] > 0.f ? 1.0f / tot[u] : 0.f;
+        const f32x4 r = acc[u] * inv;
+        const int64_t out = (int64_t)it.out_rh + e0 + u * EPP;
+        if (a.o_is_f32) {
+          __builtin_nontemporal_store(r, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.o) + out * D + ln * 4));
+        } else {
+          u32x2 h = {pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3])};
+          __builtin_nontemporal_store(h, reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.o) + out * D + ln * 4));
+        }
+        if (ln == 0) a.lse[out] = tot[u] > 0.f ? mx[u] + __logf(tot[u]) : -INFINITY;
+      }
+      s_in_chunk = 0; chunk++;
+    }
+  };
+  constexpr int NBUF = 3;               // two steps in flight + the one being folded (three in flight: no faster)
+  Buf b[NBUF];
+#pragma unroll
+  for (int k = 0; k < NBUF - 1; k++) load(k, b[k]);
+  for (int t = 0; t < n_steps; t += NBUF) {
+#pragma unroll
+    for (int k = 0; k < NBUF; k++) {
+      if (t + k < n_steps) {
+        load(t + k + NBUF - 1, b[(k + NBUF - 1) % NBUF]);
+        fold(b[k]);
+      }
     }
   }
 }
