@@ -664,3 +664,17 @@ def test_packed_blocks_through_the_other_entry_points(case):
     for name in ("dq", "dk", "dv"):
         want = torch.from_numpy(a[name]).to(torch.bfloat16).float().numpy()
         assert np.array_equal(want, b[name]), name
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_packed_blocks_of_many_tiny_sequences(seed):
+    """Blocks packed from dozens of sequences of 1 to 40 tokens (members far shorter than any tile, block lengths that are no
+    multiple of a tile), causal and not, odd and even head groups, with the dS-spill and the recomputing backward."""
+    rng = np.random.default_rng(900 + seed)
+    bs = int(rng.choice([128, 256, 384]))
+    lens = [int(x) for x in rng.integers(1, 41, size=int(rng.integers(20, 60)))] + [int(rng.integers(bs, 3 * bs))]
+    causal = int(seed % 2 == 0)
+    hq, hkv, d = [(4, 2, 64), (6, 2, 128), (8, 8, 128), (3, 1, 64)][seed]
+    wl = workloads.custom_workload(lens, bs, causal, 2, hq, hkv, d, seed=900 + seed, name=f"tiny-members-{seed}")
+    _packed_parity(wl, F32 | 16)
+    _packed_parity(wl, F32)
